@@ -1,0 +1,195 @@
+"""Plain fp64 CPU oracle of the SamKV hot path.  TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product path may import this module: it exists so that tests,
+the smoke check and the benchmark's CPU-baseline leg can compare the HIP
+kernels against an independent, slow, obviously-correct statement of what the
+paper computes.  It shares no code with the HIP library or its binding.
+
+Every function works in numpy float64, one step of the method per function, in
+the order and notation of the paper:
+
+  pooled_query         Sec. 3.1 "Generate generic query vector": Q_que by mean pooling
+  local_query          Sec. 3.1 "Add personalized bias": a document's local Q cache as one vector
+  personalized_query   Eq. 1: Q^_doc-i = Q_que + 1/(D-1) * sum_{j != i} |cos(Q_que, Q_doc-j_loc)| Q_doc-j_loc
+  score                Sec. 3.2 / Table 2: inner product <Q^_doc-i, K>
+  kept_count           budget ratio -> number of kept tokens per document and head
+  select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
+  gather               Sec. 3.2: concatenate the kept K/V of all documents in their original order
+  attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
+                       incremental prefill of the user query (no mask): softmax(q k^T * scale) v
+
+Readings taken where the paper is silent (listed once more in the design notes):
+the local Q cache becomes a vector by the same mean pooling as Q_que; under
+grouped-query attention the score of a KV head is the mean over its query
+heads; scores are raw inner products (no 1/sqrt(d), no softmax); ties in the
+selection go to the lower position; with one document the bias term vanishes;
+a cosine with a zero-norm argument counts as 0.
+
+Parity status: every function here is pinned by tests/test_oracle_pins.py
+(closed forms, hand-worked cases, brute force, library routines).  The quality
+of the whole pipeline (the paper's F1 tables) needs datasets and weights and is
+parity unpinned.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- Eq. 1
+def pooled_query(q_tok: np.ndarray) -> np.ndarray:
+    """Q_que[h, :] = mean over the query's tokens of Q[h, t, :].   q_tok [Hq, Lq, d] -> [Hq, d]."""
+    q_tok = np.asarray(q_tok, F64)
+    return q_tok.sum(axis=1) / q_tok.shape[1]
+
+
+def local_query(q_loc: np.ndarray) -> np.ndarray:
+    """Q_doc-j_loc as one vector per head: mean over the rows of the local Q cache.
+
+    q_loc [N, Hq, Wloc, d] -> [N, Hq, d]."""
+    q_loc = np.asarray(q_loc, F64)
+    return q_loc.sum(axis=2) / q_loc.shape[2]
+
+
+def abs_cos(a: np.ndarray, b: np.ndarray) -> float:
+    """|cos(a, b)| over the channels of one head; 0 when either norm is (numerically) zero."""
+    na = math.sqrt(float(np.dot(a, a)))
+    nb = math.sqrt(float(np.dot(b, b)))
+    if na < 1e-20 or nb < 1e-20:
+        return 0.0
+    return abs(float(np.dot(a, b)) / (na * nb))
+
+
+def personalized_query(q_tok: np.ndarray, q_loc: Optional[np.ndarray], n_ctx: int) -> np.ndarray:
+    """Eq. 1 for every document i and query head h.  Returns Q^ [N, Hq, d]."""
+    q_que = pooled_query(q_tok)                       # [Hq, d]
+    hq, d = q_que.shape
+    q_hat = np.empty((n_ctx, hq, d), F64)
+    if q_loc is None or n_ctx == 1:
+        q_hat[:] = q_que[None]
+        return q_hat
+    loc = local_query(q_loc)                          # [N, Hq, d]
+    assert loc.shape == (n_ctx, hq, d)
+    for i in range(n_ctx):
+        for h in range(hq):
+            bias = np.zeros(d, F64)
+            for j in range(n_ctx):
+                if j == i:
+                    continue
+                bias += abs_cos(q_que[h], loc[j, h]) * loc[j, h]
+            q_hat[i, h] = q_que[h] + bias / (n_ctx - 1)
+    return q_hat
+
+
+# --------------------------------------------------------------------------- scoring
+def score(q_hat: np.ndarray, k: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """s[i][g, t] = (1/G) * sum_{h in group g} <Q^_i[h], K_i[g, t, :]>.
+
+    q_hat [N, Hq, d]; k[i] [Hkv, L_i, d].  Returns one [Hkv, L_i] array per document."""
+    n_ctx, hq, d = q_hat.shape
+    out = []
+    for i in range(n_ctx):
+        ki = np.asarray(k[i], F64)
+        hkv, L, _ = ki.shape
+        G = hq // hkv
+        s = np.zeros((hkv, L), F64)
+        for g in range(hkv):
+            for h in range(g * G, (g + 1) * G):
+                s[g] += ki[g] @ q_hat[i, h]
+            s[g] /= G
+        out.append(s)
+    return out
+
+
+# --------------------------------------------------------------------------- selection
+def kept_count(length: int, ratio: float) -> int:
+    """Tokens kept per document and KV head: ceil(ratio * length), at least 1, at most length.
+
+    The ratio is taken at float32 precision (what crosses the C boundary); the product is shrunk
+    by 2^-22 (four float32 ulps) so that a budget that is integral in exact arithmetic, such as
+    0.1 * 20, is not pushed up by the float32 rounding of the ratio."""
+    r = float(np.float32(ratio))
+    return int(min(length, max(1, math.ceil(r * length * (1.0 - 2.0 ** -22)))))
+
+
+def select_row(scores: np.ndarray, k: int, n_sink: int = 0, n_local: int = 0) -> np.ndarray:
+    """Positions of the k kept tokens of one (document, KV head) row, ascending.
+
+    The first n_sink and last n_local positions are kept unconditionally (they count towards k);
+    the rest of the budget goes to the largest scores, equal scores to the lower position."""
+    L = scores.shape[0]
+    assert 0 < k <= L and n_sink + n_local <= k
+    forced = set(range(n_sink)) | set(range(L - n_local, L))
+    order = sorted((p for p in range(L) if p not in forced), key=lambda p: (-scores[p], p))
+    kept = sorted(forced | set(order[: k - len(forced)]))
+    return np.asarray(kept, np.int32)
+
+
+def select(scores: Sequence[np.ndarray], ratio: float, n_sink: int = 0, n_local: int = 0
+           ) -> Tuple[np.ndarray, np.ndarray]:
+    """Selection for every document and KV head.
+
+    Returns idx [Hkv, M] (document-local positions, documents in order, ascending inside each)
+    and cu_k [N+1] with M = cu_k[-1]."""
+    hkv = scores[0].shape[0]
+    ks = [kept_count(s.shape[1], ratio) for s in scores]
+    cu_k = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+    idx = np.empty((hkv, int(cu_k[-1])), np.int32)
+    for i, s in enumerate(scores):
+        for g in range(hkv):
+            idx[g, cu_k[i]:cu_k[i + 1]] = select_row(np.asarray(s[g], F64), ks[i], n_sink, n_local)
+    return idx, cu_k
+
+
+# --------------------------------------------------------------------------- compaction
+def gather(k: Sequence[np.ndarray], v: Sequence[np.ndarray], idx: np.ndarray, cu_k: np.ndarray
+           ) -> Tuple[np.ndarray, np.ndarray]:
+    """K_c[g, cu_k[i] + m, :] = K_i[g, idx[g, cu_k[i] + m], :], same for V.  Returns [Hkv, M, d] each."""
+    hkv, M = idx.shape
+    d = k[0].shape[2]
+    k_c = np.empty((hkv, M, d), k[0].dtype)
+    v_c = np.empty((hkv, M, d), v[0].dtype)
+    for i in range(len(k)):
+        for g in range(hkv):
+            for m in range(int(cu_k[i]), int(cu_k[i + 1])):
+                k_c[g, m, :] = k[i][g, idx[g, m], :]
+                v_c[g, m, :] = v[i][g, idx[g, m], :]
+    return k_c, v_c
+
+
+# --------------------------------------------------------------------------- attention
+def attention(q: np.ndarray, k_c: np.ndarray, v_c: np.ndarray, scale: float, causal: bool,
+              rows: Optional[Sequence[int]] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Softmax attention of query rows over the compacted cache.
+
+    q [Hq, R, d]; k_c, v_c [Hkv, M, d]; query head h reads KV head h // (Hq / Hkv).
+    causal=True is the recomputation of the kept tokens: row p (R == M) sees keys 0..p, itself
+    included, across document boundaries.  causal=False is the user query's prefill over the cache.
+    `rows` restricts the computation to those row numbers (outputs then have len(rows) rows).
+    Returns O [Hq, R', d] and LSE [Hq, R'] = log sum_j exp(scale * q.k_j)."""
+    q = np.asarray(q, F64)
+    k_c = np.asarray(k_c, F64)
+    v_c = np.asarray(v_c, F64)
+    hq, R, d = q.shape
+    hkv, M, _ = k_c.shape
+    G = hq // hkv
+    if causal:
+        assert R == M
+    sel = list(range(R)) if rows is None else [int(r) for r in rows]
+    out = np.empty((hq, len(sel), d), F64)
+    lse = np.empty((hq, len(sel)), F64)
+    for h in range(hq):
+        g = h // G
+        for n, p in enumerate(sel):
+            last = p + 1 if causal else M
+            s = (k_c[g, :last] @ q[h, p]) * scale
+            m = s.max()
+            e = np.exp(s - m)
+            z = e.sum()
+            out[h, n] = (e / z) @ v_c[g, :last]
+            lse[h, n] = m + math.log(z)
+    return out, lse
