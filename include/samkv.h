@@ -1,0 +1,146 @@
+/*
+ * samkv.h - C ABI of the SamKV hot path on one MI355X (gfx950).
+ *
+ * SamKV (Sparse Attention across Multiple-context KV Cache) sparsifies N independently prefilled
+ * per-document KV caches against the user query, then recomputes the kept tokens locally so that
+ * they see the other documents.  This library holds the data-parallel part of one layer:
+ *
+ *   samkv_score           personalized query vector per document (Sec. 3.1, Eq. 1) and the inner
+ *                         product of every cached key with it (Sec. 3.2, Table 2 "<.,.>")
+ *   samkv_topk_select     per document and KV head, keep the top share of the scores (Sec. 3.2);
+ *                         initial and local positions may be forced in (Sec. 3.2, Setup)
+ *   samkv_gather          concatenate the kept K/V of all documents into one compacted cache, in
+ *                         document order and original position order (Sec. 3.2, last paragraph)
+ *   samkv_recompute_attn  attention of the kept tokens over the compacted cache, causal across
+ *                         document boundaries: the attention inside the recomputation (Sec. 3.3)
+ *   samkv_query_attn      attention of the user query's tokens over the compacted cache: the final
+ *                         incremental prefill of the query (Sec. 3.3, last paragraph)
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer unless the comment says "host".  Host arrays (len,
+ *     pointer tables, cu_k_host) are read or written before the call returns.
+ *   - The caller owns every buffer, including the workspace; the library allocates nothing and keeps
+ *     no state between calls.  A workspace of samkv_workspace_bytes(...) bytes, 256-byte aligned,
+ *     serves any of the calls; its contents are scratch.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *     No call synchronises with the device.
+ *   - Tensors are dense, row-major, innermost dimension = head_dim.  `dtype` is the storage type of
+ *     K, V and all Q tensors.  Scores, attention outputs and log-sum-exp are always float32.
+ *   - Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Return value: SAMKV_OK or a negative error.  Argument errors are found before anything is
+ *     launched and leave the outputs untouched.  Results are deterministic (no float atomics).
+ *   - Limits: head_dim in {64, 128}; n_ctx <= SAMKV_MAX_CTX; each document at most SAMKV_MAX_LEN
+ *     tokens; n_q_heads a multiple of n_kv_heads.
+ */
+#ifndef SAMKV_H_
+#define SAMKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAMKV_MAX_CTX 128
+#define SAMKV_MAX_LEN 65536
+
+typedef enum { SAMKV_F32 = 0, SAMKV_BF16 = 1 } samkv_dtype;
+
+enum {
+  SAMKV_OK = 0,
+  SAMKV_EINVAL = -1,       /* NULL pointer, non-positive size, inconsistent shapes, ratio outside (0, 1] */
+  SAMKV_EUNSUPPORTED = -2, /* head_dim, dtype, n_ctx or document length outside the limits above */
+  SAMKV_EWORKSPACE = -3,   /* workspace missing or smaller than samkv_workspace_bytes(...) */
+  SAMKV_EDEVICE = -4       /* the HIP runtime refused a launch */
+};
+
+/* The N independently stored per-document caches of one layer (problem statement of the paper:
+ * "each document's KV Cache is computed and stored independently").  Host struct. */
+typedef struct {
+  int32_t n_ctx;            /* D in the paper: number of documents                              */
+  int32_t n_q_heads;        /* Hq                                                                */
+  int32_t n_kv_heads;       /* Hkv                                                               */
+  int32_t head_dim;         /* d                                                                 */
+  int32_t dtype;            /* samkv_dtype of k, v and of every Q tensor passed with this struct */
+  const int32_t* len;       /* host [n_ctx]: tokens per document, each >= 1                      */
+  const void* const* k;     /* host [n_ctx] of device pointers, document i: [Hkv][len[i]][d]     */
+  const void* const* v;     /* same for V; may be NULL for samkv_score and samkv_topk_select     */
+} samkv_caches;
+
+/* Human-readable name of an error code (static string). */
+const char* samkv_strerror(int code);
+
+/* Number of tokens kept per (document, KV head) for a document of `len` tokens at budget `ratio`:
+ * ceil(ratio * len), at least 1, at most len; the product is shrunk by 2^-22 before the ceiling so
+ * that the float32 rounding of the ratio cannot push an integral budget up (0.1 * 20 gives 2).
+ * Returns 0 for invalid arguments. */
+int32_t samkv_kept_count(int32_t len, float ratio);
+
+/* Bytes of workspace that serve every call below for these sizes.  m_total = sum of kept counts
+ * (length of the compacted cache); n_q_tok = user-query tokens; w_loc = rows of a local Q cache. */
+size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int32_t n_q_tok, int32_t m_total);
+
+/* Sec. 3.1 + Sec. 3.2 scoring.
+ *   Q_que[h]     = mean over the n_q_tok rows of q_tok[h]                      (generic query vector)
+ *   Q_loc_j[h]   = mean over the w_loc rows of q_loc[j][h]                     (document j's local Q cache)
+ *   Q^_i[h]      = Q_que[h] + 1/(N-1) * sum_{j != i} |cos(Q_que[h], Q_loc_j[h])| * Q_loc_j[h]      (Eq. 1)
+ *   scores[g][cu_len[i] + t] = mean over the query heads h of KV head g of <Q^_i[h], K_i[g][t][:]>
+ * with cu_len the exclusive prefix sum of caches->len.  q_loc == NULL or n_ctx == 1 drops the bias
+ * term; a cosine whose argument has norm below 1e-20 counts as 0.
+ *   q_tok   [Hq][n_q_tok][d]            dtype of caches
+ *   q_loc   [n_ctx][Hq][w_loc][d]       dtype of caches, or NULL
+ *   scores  [Hkv][sum len]  float32     written
+ * Arithmetic: float32 accumulation of exact products. */
+int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                int32_t w_loc, float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.2 selection with a fixed budget.  For document i and KV head g, keep k_i =
+ * samkv_kept_count(len[i], ratio) positions: first the n_sink initial and n_local last positions
+ * (they count towards k_i; n_sink + n_local > k_i for any document is SAMKV_EINVAL), then the
+ * largest scores; equal scores go to the lower position.
+ *   scores     [Hkv][sum len] float32, as written by samkv_score
+ *   idx        [Hkv][M] int32 written: document-local positions, documents in order, ascending
+ *              inside each document; M = sum k_i
+ *   cu_k_dev   [n_ctx + 1] int32 device, written (exclusive prefix sum of k_i); may be NULL
+ *   cu_k_host  [n_ctx + 1] int32 host, written before the call returns; may be NULL
+ * caches->k and caches->v are not read. */
+int samkv_topk_select(const float* scores, const samkv_caches* caches, float ratio, int32_t n_sink,
+                      int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws,
+                      size_t ws_bytes, void* stream);
+
+/* Sec. 3.2 compaction: K_c[g][cu_k[i] + m][:] = K_i[g][idx[g][cu_k[i] + m]][:], same for V; bit-exact
+ * copies.  The kept counts are recomputed from caches->len and `ratio` exactly as in
+ * samkv_topk_select, so idx must come from a selection at the same ratio.
+ *   idx   [Hkv][M] int32 device (values outside [0, len[i]) are clamped, never dereferenced raw)
+ *   k_c, v_c  [Hkv][M][d]  dtype of caches, written */
+int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, void* k_c, void* v_c,
+                 void* stream);
+
+/* Sec. 3.3 recomputation, attention part.  Row p of query head h is the query state of the token
+ * that KV head g(h) keeps at compacted position p; it attends to compacted positions 0..p (itself
+ * included), across document boundaries:
+ *   out[h][p][:] = sum_{j <= p} softmax_j(scale * <q_rec[h][p], k_c[g][j]>) * v_c[g][j]
+ *   lse[h][p]    = log sum_{j <= p} exp(scale * <q_rec[h][p], k_c[g][j]>)
+ *   q_rec [Hq][M][d], k_c, v_c [Hkv][M][d] in `dtype`; out [Hq][M][d], lse [Hq][M] float32.
+ * bf16: products on the bf16 matrix cores, softmax statistics and accumulators float32, the
+ * softmax weights are rounded to bf16 before they multiply V.  f32: float32 throughout. */
+int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                         float scale, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.3, last paragraph: the user query's tokens attend over the whole compacted cache (every
+ * cached token precedes the query, so there is no mask):
+ *   out[h][t][:] = sum_{j < M} softmax_j(scale * <q_tok[h][t], k_c[g][j]>) * v_c[g][j],  lse likewise.
+ *   q_tok [Hq][n_q_tok][d]; out [Hq][n_q_tok][d], lse [Hq][n_q_tok] float32.
+ * Arithmetic as in samkv_recompute_attn. */
+int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
+                     int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                     int32_t dtype, float scale, float* out, float* lse, void* ws, size_t ws_bytes,
+                     void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMKV_H_ */

@@ -1,0 +1,412 @@
+// Attention over the compacted multi-document cache (Sec. 3.3):
+//   causal     - recomputation of the kept tokens: row p sees compacted positions 0..p
+//   not causal - the user query's final incremental prefill over the whole compacted cache
+// Both are softmax(scale * q k^T) v with float32 statistics; they differ in the mask and in how the
+// rows are cut into workgroups, so one kernel template serves both.
+//
+// bf16 kernel (k_attn_bf16), one workgroup = 4 waves = 128 query rows, 64 keys per step:
+//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = the wave's 32 query rows (registers,
+//                 loaded once).  Computing the transpose puts one query row in one lane column, so the
+//                 softmax weights come out of the accumulator already in the B-operand layout of the
+//                 next product and never travel through LDS.
+//   O^T += V^T P^T  same instruction, A = V^T read from the row-major V tile in LDS with the
+//                 transposing LDS read (ds_read_b64_tr_b16), B = P^T (bf16) from registers.
+//   K/V tiles are double-buffered in LDS; the next tile's global loads are issued before the current
+//   tile's math and land in LDS after it, one barrier per tile.
+// f32 kernel (k_attn_f32): plain FMA arithmetic for float32 caches, 16 rows per workgroup.
+// Keys can be cut into chunks (not causal only); k_attn_merge combines the per-chunk results with
+// their log-sum-exp.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace samkv {
+namespace {
+
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  float* out;
+  float* lse;
+  float* part_o;
+  float* part_lse;
+  int rows, m, batch_per_kv, n_batch, n_split, chunk;
+  float scale;
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ------------------------------------------------------------------------------------------ bf16
+template <int D>
+struct Bf16Cfg {
+  static constexpr int BQ = 128, BK = 64;
+  static constexpr int KSTR = D * 2 + 16;  // bytes per K row in LDS (pad: 16 rows hit 64 distinct banks)
+  static constexpr int VSTR = D * 2 + 32;  // bytes per V row in LDS (pad: 4 rows x 32 B of a transposing read are disjoint)
+  static constexpr int TILE_BYTES = BK * (KSTR + VSTR);
+  static constexpr int LDS_BYTES = 2 * TILE_BYTES;
+  static constexpr int CHUNKS = (BK * D * 2 / 16) / 256;  // 16-byte chunks per thread per tile and tensor
+};
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
+  using C = Bf16Cfg<D>;
+  constexpr int ND = D / 16;   // k-steps of the S^T product
+  constexpr int NV = D / 32;   // 32-row blocks of O^T
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int rw = lane & 31, h = lane >> 5;
+  const int qt = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;  // long causal tiles first
+  const int q0 = qt * C::BQ;
+  const int batch = blockIdx.y, split = blockIdx.z;
+  const int kvh = batch / a.batch_per_kv;
+  const int kv_begin = CAUSAL ? 0 : split * a.chunk;
+  const int kv_end = CAUSAL ? min(a.m, q0 + C::BQ) : min(a.m, kv_begin + a.chunk);
+  const int n_tiles = (kv_end - kv_begin + C::BK - 1) / C::BK;
+
+  const int r = q0 + wave * 32 + rw;
+  const int r_c = min(r, a.rows - 1);
+  const int wave_first = q0 + wave * 32, wave_last = wave_first + 31;
+
+  bf16x8 bq[ND];
+  {
+    const char* qp = static_cast<const char*>(a.q) + ((size_t)batch * a.rows + r_c) * D * 2 + h * 16;
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) bq[dc] = *reinterpret_cast<const bf16x8*>(qp + dc * 32);
+  }
+  const char* kbase = static_cast<const char*>(a.k) + (size_t)kvh * a.m * D * 2;
+  const char* vbase = static_cast<const char*>(a.v) + (size_t)kvh * a.m * D * 2;
+
+  u32x4 rk[C::CHUNKS], rv[C::CHUNKS];
+  auto load_tile = [&](int tile) {
+    const int k0 = kv_begin + tile * C::BK;
+#pragma unroll
+    for (int i = 0; i < C::CHUNKS; ++i) {
+      const int c = t + 256 * i;
+      const int row = c / (D / 8), col = c % (D / 8);
+      const int key = min(k0 + row, a.m - 1);
+      const size_t off = (size_t)key * D * 2 + col * 16;
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + off);
+      rv[i] = *reinterpret_cast<const u32x4*>(vbase + off);
+    }
+  };
+  auto store_tile = [&](int buf) {
+    char* sk = smem + buf * C::TILE_BYTES;
+    char* sv = sk + C::BK * C::KSTR;
+#pragma unroll
+    for (int i = 0; i < C::CHUNKS; ++i) {
+      const int c = t + 256 * i;
+      const int row = c / (D / 8), col = c % (D / 8);
+      *reinterpret_cast<u32x4*>(sk + row * C::KSTR + col * 16) = rk[i];
+      *reinterpret_cast<u32x4*>(sv + row * C::VSTR + col * 16) = rv[i];
+    }
+  };
+
+  f32x16 o[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c2 = a.scale * kLog2e;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int k0 = kv_begin + tile * C::BK;
+    const bool more = tile + 1 < n_tiles;
+    if (more) load_tile(tile + 1);
+
+    const bool active = !CAUSAL || k0 <= wave_last;
+    if (active) {
+      const char* sk = smem + (tile & 1) * C::TILE_BYTES;
+      const char* sv = sk + C::BK * C::KSTR;
+      f32x16 s[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+#pragma unroll
+        for (int dc = 0; dc < ND; ++dc) {
+          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + rw) * C::KSTR + dc * 32 + h * 16);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[dc], s[kb], 0, 0, 0);
+        }
+      }
+      // accumulator register j of block kb holds key k0 + kb*32 + 8*(j/4) + 4*h + (j%4) for row r
+      const bool need_mask = (CAUSAL && k0 + C::BK - 1 > wave_first) || (k0 + C::BK > kv_end);
+      if (need_mask) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const int key = k0 + kb * 32 + 8 * (j >> 2) + 4 * h + (j & 3);
+            if (key >= kv_end || (CAUSAL && key > r)) s[kb][j] = -INFINITY;
+          }
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][j]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx * c2);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][j], c2, -m_use));
+          s[kb][j] = p;
+          psum += p;
+        }
+      l_run = fmaf(l_run, alpha, psum);
+      if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
+      }
+      const int i16 = lane & 15, q2 = (lane >> 4) & 1;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          bf16x8 bp;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) bp[e] = (__bf16)s[kb][8 * s2 + e];
+          const int key1 = kb * 32 + 16 * s2 + 4 * h + (i16 >> 2);
+#pragma unroll
+          for (int dvb = 0; dvb < NV; ++dvb) {
+            const char* vp = sv + key1 * C::VSTR + (dvb * 32 + q2 * 16 + 4 * (i16 & 3)) * 2;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * C::VSTR));
+            union { struct { s16x4 lo, hi; } s; bf16x8 v; } av;
+            av.s.lo = lo;
+            av.s.hi = hi;
+            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp, o[dvb], 0, 0, 0);
+          }
+        }
+    }
+    if (more) store_tile((tile + 1) & 1);
+    __syncthreads();
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = 1.f / l_tot;
+  if (r < a.rows) {
+    const size_t row_id = (size_t)batch * a.rows + r;
+    float* op;
+    float* lp;
+    if (a.n_split > 1) {
+      const size_t prow = (size_t)split * a.n_batch * a.rows + row_id;
+      op = a.part_o + prow * D;
+      lp = a.part_lse + prow;
+    } else {
+      op = a.out + row_id * D;
+      lp = a.lse + row_id;
+    }
+#pragma unroll
+    for (int dvb = 0; dvb < NV; ++dvb)
+#pragma unroll
+      for (int j4 = 0; j4 < 4; ++j4) {
+        f32x4 x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
+        *reinterpret_cast<f32x4*>(op + dvb * 32 + 8 * j4 + 4 * h) = x;
+      }
+    if (h == 0) *lp = (m_run + __log2f(l_tot)) * kLn2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------- f32
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
+  constexpr int BK = 32, R = 4, RB = 16, KS = D + 1, NC = D / 64;
+  __shared__ float sK[BK * KS];
+  __shared__ float sV[BK * D];
+  __shared__ float sQ[RB * D];
+  __shared__ float sP[RB * BK];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int kx = lane & 31, ch = lane >> 5;
+  const int qt = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const int q0 = qt * RB;
+  const int batch = blockIdx.y, split = blockIdx.z;
+  const int kvh = batch / a.batch_per_kv;
+  const int kv_begin = CAUSAL ? 0 : split * a.chunk;
+  const int kv_end = CAUSAL ? min(a.m, q0 + RB) : min(a.m, kv_begin + a.chunk);
+  const int n_tiles = (kv_end - kv_begin + BK - 1) / BK;
+  const float* q = static_cast<const float*>(a.q);
+  const float* kbase = static_cast<const float*>(a.k) + (size_t)kvh * a.m * D;
+  const float* vbase = static_cast<const float*>(a.v) + (size_t)kvh * a.m * D;
+
+  for (int i = t; i < RB * D; i += 256) {
+    const int rc = min(q0 + i / D, a.rows - 1);
+    sQ[i] = q[((size_t)batch * a.rows + rc) * D + i % D];
+  }
+  float m_run[R], l_run[R], o[R][NC];
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    m_run[rr] = -INFINITY;
+    l_run[rr] = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) o[rr][cc] = 0.f;
+  }
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int k0 = kv_begin + tile * BK;
+    __syncthreads();
+    for (int i = t; i < BK * D; i += 256) {
+      const int row = i / D, c = i % D;
+      const size_t off = (size_t)min(k0 + row, a.m - 1) * D + c;
+      sK[row * KS + c] = kbase[off];
+      sV[row * D + c] = vbase[off];
+    }
+    __syncthreads();
+    float s[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) s[rr] = 0.f;
+    for (int i = 0; i < D / 2; ++i) {
+      // the two half-waves walk the channels half a bank cycle apart
+      const int c = ch ? D / 2 + ((i + 32) % (D / 2)) : i;
+      const float kv = sK[kx * KS + c];
+#pragma unroll
+      for (int rr = 0; rr < R; ++rr) s[rr] = fmaf(sQ[(wave * R + rr) * D + c], kv, s[rr]);
+    }
+    const int key = k0 + kx;
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+      const int row = q0 + wave * R + rr;
+      float x = s[rr] + __shfl_xor(s[rr], 32);
+      x = (key >= kv_end || (CAUSAL && key > row)) ? -INFINITY : x * a.scale;
+      float mx = x;
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      const float m_new = fmaxf(m_run[rr], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float p = expf(x - m_use);
+      float sum = p;
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+      const float alpha = expf(m_run[rr] - m_use);
+      l_run[rr] = l_run[rr] * alpha + sum;
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) o[rr][cc] *= alpha;
+      m_run[rr] = m_new;
+      if (ch == 0) sP[(wave * R + rr) * BK + kx] = p;
+    }
+    __syncthreads();
+    for (int j = 0; j < BK; ++j) {
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) {
+        const float vv = sV[j * D + lane + 64 * cc];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) o[rr][cc] = fmaf(sP[(wave * R + rr) * BK + j], vv, o[rr][cc]);
+      }
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    const int row = q0 + wave * R + rr;
+    if (row >= a.rows) continue;
+    const size_t row_id = (size_t)batch * a.rows + row;
+    float* op;
+    float* lp;
+    if (a.n_split > 1) {
+      const size_t prow = (size_t)split * a.n_batch * a.rows + row_id;
+      op = a.part_o + prow * D;
+      lp = a.part_lse + prow;
+    } else {
+      op = a.out + row_id * D;
+      lp = a.lse + row_id;
+    }
+    const float inv = 1.f / l_run[rr];
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) op[lane + 64 * cc] = o[rr][cc] * inv;
+    if (lane == 0) *lp = m_run[rr] + logf(l_run[rr]);
+  }
+}
+
+// out = sum_s w_s * part_o[s] with w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One thread per
+// channel, one block per 256 / d rows; splits are visited in order, so the result is deterministic.
+__global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a, int d) {
+  const int rpb = 256 / d;
+  const size_t n_rows = (size_t)a.n_batch * a.rows;
+  const size_t row = (size_t)blockIdx.x * rpb + threadIdx.x / d;
+  const int c = threadIdx.x % d;
+  if (row >= n_rows) return;
+  float mx = -INFINITY;
+  for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, a.part_lse[(size_t)s * n_rows + row]);
+  float den = 0.f, acc = 0.f;
+  for (int s = 0; s < a.n_split; ++s) {
+    const float w = expf(a.part_lse[(size_t)s * n_rows + row] - mx);
+    den += w;
+    acc = fmaf(w, a.part_o[((size_t)s * n_rows + row) * d + c], acc);
+  }
+  a.out[row * d + c] = acc / den;
+  if (c == 0) a.lse[row] = mx + logf(den);
+}
+
+AttnArgs make_args(const AttnLaunch& l) {
+  AttnArgs a;
+  a.q = l.q; a.k = l.k; a.v = l.v; a.out = l.out; a.lse = l.lse;
+  a.part_o = l.part_o; a.part_lse = l.part_lse;
+  a.rows = l.rows; a.m = l.m; a.batch_per_kv = l.batch_per_kv; a.n_batch = l.n_batch;
+  a.n_split = l.causal ? 1 : l.n_split;
+  a.chunk = l.chunk; a.scale = l.scale;
+  return a;
+}
+
+template <int D, bool CAUSAL>
+hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
+  using C = Bf16Cfg<D>;
+  static bool attr_set = false;  // per process; the attribute belongs to the function, not the stream
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  AttnArgs a = make_args(l);
+  dim3 grid((l.rows + C::BQ - 1) / C::BQ, l.n_batch, a.n_split);
+  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL>), grid, dim3(256), C::LDS_BYTES, s, a);
+  return hipGetLastError();
+}
+
+template <int D, bool CAUSAL>
+hipError_t run_f32(const AttnLaunch& l, hipStream_t s) {
+  AttnArgs a = make_args(l);
+  dim3 grid((l.rows + 15) / 16, l.n_batch, a.n_split);
+  hipLaunchKernelGGL((k_attn_f32<D, CAUSAL>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
+  if (l.d == 128) return l.causal ? run_bf16<128, true>(l, s) : run_bf16<128, false>(l, s);
+  return l.causal ? run_bf16<64, true>(l, s) : run_bf16<64, false>(l, s);
+}
+
+hipError_t launch_attn_f32(const AttnLaunch& l, hipStream_t s) {
+  if (l.d == 128) return l.causal ? run_f32<128, true>(l, s) : run_f32<128, false>(l, s);
+  return l.causal ? run_f32<64, true>(l, s) : run_f32<64, false>(l, s);
+}
+
+hipError_t launch_attn_merge(const AttnLaunch& l, hipStream_t s) {
+  AttnArgs a = make_args(l);
+  const int rpb = 256 / l.d;
+  const size_t n_rows = (size_t)l.n_batch * l.rows;
+  hipLaunchKernelGGL(k_attn_merge, dim3((unsigned)((n_rows + rpb - 1) / rpb)), dim3(256), 0, s, a, l.d);
+  return hipGetLastError();
+}
+
+}  // namespace samkv

@@ -1,0 +1,91 @@
+// Shared declarations of the SamKV HIP library (gfx950 only): kernel-argument tables, small device
+// helpers and the host-side launch entry points that samkv_api.hip calls.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/samkv.h"
+
+namespace samkv {
+
+// Per-document pointers and prefix sums travel to the kernels by value in the kernel-argument
+// segment (no device allocation, no host-to-device copy, nothing for a later call to race with).
+struct PtrTable {
+  const void* p[SAMKV_MAX_CTX];
+};
+struct IntTable {
+  int32_t v[SAMKV_MAX_CTX + 1];
+};
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// document that owns compacted position m: largest i with cu[i] <= m
+__device__ __forceinline__ int find_ctx(const IntTable& cu, int n_ctx, int m) {
+  int lo = 0, hi = n_ctx;  // invariant: cu[lo] <= m < cu[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu.v[mid] <= m) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ---- host-side launchers (one per translation unit) -------------------------------------------
+struct ScoreLaunch {
+  int n_ctx, hq, hkv, d, dtype, n_q_tok, w_loc, max_len, total_len;
+  const void* q_tok;
+  const void* q_loc;  // may be null
+  float* scores;
+  float* ws_que;    // [Hq][d]
+  float* ws_loc;    // [N][Hq][d]
+  float* ws_w;      // [N][Hq]
+  float* ws_qt;     // [N][Hkv][d]
+};
+hipError_t launch_score(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s);
+
+struct SelectLaunch {
+  int n_ctx, hkv, max_len, total_len, m_total, n_sink, n_local;
+  const float* scores;
+  int32_t* idx;
+  int32_t* cu_k_dev;  // may be null
+};
+hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s);
+
+struct GatherLaunch {
+  int n_ctx, hkv, row_bytes, m_total;
+  const int32_t* idx;
+  void* k_c;
+  void* v_c;
+};
+hipError_t launch_gather(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
+                         const IntTable& cu_k, hipStream_t s);
+
+// One attention problem: `n_batch` independent row blocks, batch b reads KV head b / batch_per_kv.
+// Row r of a batch attends keys [0, r] (causal) or [0, m) (not causal).
+struct AttnLaunch {
+  int dtype, d, causal;
+  int n_batch, batch_per_kv, rows, m;
+  const void* q;   // [n_batch][rows][d]
+  const void* k;   // [n_batch / batch_per_kv][m][d]
+  const void* v;
+  float* out;      // [n_batch][rows][d]
+  float* lse;      // [n_batch][rows]
+  float scale;
+  int n_split, chunk;  // keys are cut into n_split chunks of `chunk` keys (not causal only)
+  float* part_o;       // [n_split][n_batch][rows][d]   workspace when n_split > 1
+  float* part_lse;     // [n_split][n_batch][rows]
+};
+hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_attn_merge(const AttnLaunch& a, hipStream_t s);
+
+}  // namespace samkv

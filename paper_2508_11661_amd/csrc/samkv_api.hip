@@ -1,0 +1,245 @@
+// C ABI of the SamKV hot path: argument checks, host-side prefix sums, workspace carving and the
+// kernel launches.  Everything a call needs on the device travels in kernel arguments; the library
+// allocates nothing and synchronises with nothing.
+#include <math.h>
+#include <string.h>
+
+#include "common.hpp"
+
+using namespace samkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+int kept_count(int len, float ratio) {
+  if (len < 1 || !(ratio > 0.f) || ratio > 1.f) return 0;
+  const double x = (double)ratio * (double)len * (1.0 - 0x1p-22);
+  long long k = (long long)ceil(x);
+  if (k < 1) k = 1;
+  if (k > len) k = len;
+  return (int)k;
+}
+
+struct Shape {
+  int n_ctx, hq, hkv, d, dtype, max_len, total_len;
+  IntTable cu_len;
+};
+
+int check_caches(const samkv_caches* c, bool need_k, bool need_v, Shape* s) {
+  if (c == nullptr || c->len == nullptr) return SAMKV_EINVAL;
+  if (c->n_ctx < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0) return SAMKV_EINVAL;
+  if (c->dtype != SAMKV_F32 && c->dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return SAMKV_EUNSUPPORTED;
+  if (c->n_ctx > SAMKV_MAX_CTX) return SAMKV_EUNSUPPORTED;
+  if ((need_k && c->k == nullptr) || (need_v && c->v == nullptr)) return SAMKV_EINVAL;
+  s->n_ctx = c->n_ctx; s->hq = c->n_q_heads; s->hkv = c->n_kv_heads; s->d = c->head_dim; s->dtype = c->dtype;
+  s->max_len = 0;
+  long long total = 0;
+  s->cu_len.v[0] = 0;
+  for (int i = 0; i < c->n_ctx; ++i) {
+    if (c->len[i] < 1) return SAMKV_EINVAL;
+    if (c->len[i] > SAMKV_MAX_LEN) return SAMKV_EUNSUPPORTED;
+    if ((need_k && c->k[i] == nullptr) || (need_v && c->v[i] == nullptr)) return SAMKV_EINVAL;
+    total += c->len[i];
+    if (total > 0x7FFFFFFF / 2) return SAMKV_EUNSUPPORTED;
+    s->cu_len.v[i + 1] = (int32_t)total;
+    if (c->len[i] > s->max_len) s->max_len = c->len[i];
+  }
+  s->total_len = (int)total;
+  return SAMKV_OK;
+}
+
+int kept_table(const samkv_caches* c, float ratio, int n_sink, int n_local, IntTable* cu_k) {
+  if (!(ratio > 0.f) || ratio > 1.f || n_sink < 0 || n_local < 0) return SAMKV_EINVAL;
+  cu_k->v[0] = 0;
+  for (int i = 0; i < c->n_ctx; ++i) {
+    const int k = kept_count(c->len[i], ratio);
+    if ((long long)n_sink + n_local > k) return SAMKV_EINVAL;
+    cu_k->v[i + 1] = cu_k->v[i] + k;
+  }
+  return SAMKV_OK;
+}
+
+// Score workspace: Q_que [Hq][d], Q_loc [N][Hq][d], |cos| [N][Hq], folded vectors [N][Hkv][d], float32.
+struct ScoreWs { size_t que, loc, w, qt, bytes; };
+ScoreWs score_ws(int n_ctx, int hq, int hkv, int d) {
+  ScoreWs w;
+  size_t o = 0;
+  w.que = o; o = align_up(o + (size_t)hq * d * 4);
+  w.loc = o; o = align_up(o + (size_t)n_ctx * hq * d * 4);
+  w.w = o;   o = align_up(o + (size_t)n_ctx * hq * 4);
+  w.qt = o;  o = align_up(o + (size_t)n_ctx * hkv * d * 4);
+  w.bytes = o;
+  return w;
+}
+
+// Not-causal attention: cut the keys into chunks when the row tiles alone cannot fill the chip.
+struct SplitPlan { int n_split, chunk; size_t part_o, part_lse, bytes; };
+SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
+  const int bq = dtype == SAMKV_BF16 ? 128 : 16;
+  const int bk = dtype == SAMKV_BF16 ? 64 : 32;
+  const long long base = (long long)((rows + bq - 1) / bq) * n_batch;
+  const int key_tiles = (m + bk - 1) / bk;
+  long long want = (1024 + base - 1) / base;  // aim at ~4 workgroups per compute unit
+  if (want > key_tiles) want = key_tiles;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  int tiles_per = (int)((key_tiles + want - 1) / want);
+  SplitPlan p;
+  p.chunk = tiles_per * bk;
+  p.n_split = (m + p.chunk - 1) / p.chunk;
+  p.part_o = 0;
+  p.part_lse = 0;
+  p.bytes = 0;
+  if (p.n_split > 1) {
+    const size_t n_rows = (size_t)n_batch * rows;
+    p.part_o = 0;
+    p.part_lse = align_up((size_t)p.n_split * n_rows * d * 4);
+    p.bytes = align_up(p.part_lse + (size_t)p.n_split * n_rows * 4);
+  }
+  return p;
+}
+
+int check_attn(const void* q, const void* k, const void* v, int rows, int m, int hq, int hkv, int d, int dtype,
+               float scale, const float* out, const float* lse) {
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || lse == nullptr) return SAMKV_EINVAL;
+  if (rows < 1 || m < 1 || hq < 1 || hkv < 1 || hq % hkv != 0 || !(scale > 0.f) || !isfinite(scale)) return SAMKV_EINVAL;
+  if (dtype != SAMKV_F32 && dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
+  if (d != 64 && d != 128) return SAMKV_EUNSUPPORTED;
+  if ((long long)hq * rows > 0x7FFFFFFF / 256 || m > 0x7FFFFFFF / 512) return SAMKV_EUNSUPPORTED;
+  return SAMKV_OK;
+}
+
+int dev(hipError_t e) { return e == hipSuccess ? SAMKV_OK : SAMKV_EDEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char* samkv_strerror(int code) {
+  switch (code) {
+    case SAMKV_OK: return "ok";
+    case SAMKV_EINVAL: return "invalid argument";
+    case SAMKV_EUNSUPPORTED: return "unsupported size or dtype";
+    case SAMKV_EWORKSPACE: return "workspace missing or too small";
+    case SAMKV_EDEVICE: return "HIP launch failed";
+  }
+  return "unknown error";
+}
+
+int32_t samkv_kept_count(int32_t len, float ratio) { return kept_count(len, ratio); }
+
+size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int32_t n_q_tok, int32_t m_total) {
+  if (n_ctx < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_q_tok < 1 || m_total < 1) return 0;
+  const size_t a = score_ws(n_ctx, n_q_heads, n_kv_heads, head_dim).bytes;
+  const int rows = (n_q_heads / n_kv_heads) * n_q_tok;
+  size_t b = plan_splits(SAMKV_BF16, n_kv_heads, rows, m_total, head_dim).bytes;
+  const size_t c = plan_splits(SAMKV_F32, n_kv_heads, rows, m_total, head_dim).bytes;
+  if (c > b) b = c;
+  return (a > b ? a : b) + kAlign;
+}
+
+int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
+                float* scores, void* ws, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, true, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_tok == nullptr || scores == nullptr || n_q_tok < 1 || (q_loc != nullptr && w_loc < 1)) return SAMKV_EINVAL;
+  const ScoreWs w = score_ws(s.n_ctx, s.hq, s.hkv, s.d);
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
+  PtrTable kt;
+  memset(&kt, 0, sizeof(kt));
+  for (int i = 0; i < s.n_ctx; ++i) kt.p[i] = caches->k[i];
+  ScoreLaunch a;
+  a.n_ctx = s.n_ctx; a.hq = s.hq; a.hkv = s.hkv; a.d = s.d; a.dtype = s.dtype;
+  a.n_q_tok = n_q_tok; a.w_loc = w_loc; a.max_len = s.max_len; a.total_len = s.total_len;
+  a.q_tok = q_tok; a.q_loc = q_loc; a.scores = scores;
+  char* base = static_cast<char*>(ws);
+  a.ws_que = reinterpret_cast<float*>(base + w.que);
+  a.ws_loc = reinterpret_cast<float*>(base + w.loc);
+  a.ws_w = reinterpret_cast<float*>(base + w.w);
+  a.ws_qt = reinterpret_cast<float*>(base + w.qt);
+  return dev(launch_score(a, kt, s.cu_len, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_topk_select(const float* scores, const samkv_caches* caches, float ratio, int32_t n_sink, int32_t n_local,
+                      int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (scores == nullptr || idx == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table(caches, ratio, n_sink, n_local, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
+  SelectLaunch a;
+  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.max_len = s.max_len; a.total_len = s.total_len;
+  a.m_total = cu_k.v[s.n_ctx]; a.n_sink = n_sink; a.n_local = n_local;
+  a.scores = scores; a.idx = idx; a.cu_k_dev = cu_k_dev;
+  return dev(launch_select(a, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, void* k_c, void* v_c, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, true, true, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (idx == nullptr || k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table(caches, ratio, 0, 0, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  PtrTable kt, vt;
+  memset(&kt, 0, sizeof(kt));
+  memset(&vt, 0, sizeof(vt));
+  for (int i = 0; i < s.n_ctx; ++i) { kt.p[i] = caches->k[i]; vt.p[i] = caches->v[i]; }
+  GatherLaunch a;
+  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.row_bytes = s.d * (s.dtype == SAMKV_BF16 ? 2 : 4);
+  a.m_total = cu_k.v[s.n_ctx]; a.idx = idx; a.k_c = k_c; a.v_c = v_c;
+  return dev(launch_gather(a, kt, vt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
+                         void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  int rc = check_attn(q_rec, k_c, v_c, m_total, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
+  if (rc != SAMKV_OK) return rc;
+  AttnLaunch a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.d = head_dim; a.causal = 1;
+  a.n_batch = n_q_heads; a.batch_per_kv = n_q_heads / n_kv_heads; a.rows = m_total; a.m = m_total;
+  a.q = q_rec; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
+  a.n_split = 1; a.chunk = m_total;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  return dev(dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s));
+}
+
+int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c, int32_t m_total,
+                     int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out,
+                     float* lse, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_attn(q_tok, k_c, v_c, n_q_tok, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
+  if (rc != SAMKV_OK) return rc;
+  // q_tok [Hq][Lq][d] is, per KV head, one contiguous block of G*Lq rows that all read the same K/V.
+  const int rows = (n_q_heads / n_kv_heads) * n_q_tok;
+  const SplitPlan p = plan_splits(dtype, n_kv_heads, rows, m_total, head_dim);
+  if (p.n_split > 1 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < p.bytes)) return SAMKV_EWORKSPACE;
+  AttnLaunch a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.d = head_dim; a.causal = 0;
+  a.n_batch = n_kv_heads; a.batch_per_kv = 1; a.rows = rows; a.m = m_total;
+  a.q = q_tok; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
+  a.n_split = p.n_split; a.chunk = p.chunk;
+  if (p.n_split > 1) {
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o);
+    a.part_lse = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_lse);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  if (e == hipSuccess && p.n_split > 1) e = launch_attn_merge(a, s);
+  return dev(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,231 @@
+"""ctypes binding of libsamkv.so: the same five entry points as include/samkv.h, taking torch tensors.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of the library.  torch is
+used for device memory and for the current stream.  If the library is missing the import of this
+module fails; there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch  # noqa: F401  (must be loaded first: the library binds to the HIP runtime torch ships)
+
+SAMKV_F32, SAMKV_BF16 = 0, 1
+SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
+
+EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_workspace_bytes", "samkv_score", "samkv_topk_select",
+           "samkv_gather", "samkv_recompute_attn", "samkv_query_attn")
+
+
+class _Caches(ctypes.Structure):
+    _fields_ = [
+        ("n_ctx", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("len", ctypes.POINTER(ctypes.c_int32)),
+        ("k", ctypes.POINTER(ctypes.c_void_p)), ("v", ctypes.POINTER(ctypes.c_void_p)),
+    ]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2508_11661_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    cp = ctypes.POINTER(_Caches)
+    lib.samkv_strerror.restype = ctypes.c_char_p
+    lib.samkv_strerror.argtypes = [ctypes.c_int]
+    lib.samkv_kept_count.restype = i32
+    lib.samkv_kept_count.argtypes = [i32, f32]
+    lib.samkv_workspace_bytes.restype = sz
+    lib.samkv_workspace_bytes.argtypes = [i32] * 6
+    lib.samkv_score.restype = ctypes.c_int
+    lib.samkv_score.argtypes = [cp, vp, i32, vp, i32, vp, vp, sz, vp]
+    lib.samkv_topk_select.restype = ctypes.c_int
+    lib.samkv_topk_select.argtypes = [vp, cp, f32, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.samkv_gather.restype = ctypes.c_int
+    lib.samkv_gather.argtypes = [cp, vp, f32, vp, vp, vp]
+    lib.samkv_recompute_attn.restype = ctypes.c_int
+    lib.samkv_recompute_attn.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.samkv_query_attn.restype = ctypes.c_int
+    lib.samkv_query_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    return lib
+
+
+_lib = _load()
+
+
+class SamKVError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {_lib.samkv_strerror(code).decode()} ({code})")
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise SamKVError(code, where)
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return SAMKV_F32
+    if t == torch.bfloat16:
+        return SAMKV_BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors must be dense"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+@dataclass
+class Caches:
+    """The per-document K/V caches of one layer: k[i], v[i] are [Hkv, L_i, d] device tensors."""
+
+    k: Sequence[torch.Tensor]
+    v: Optional[Sequence[torch.Tensor]]
+    n_q_heads: int
+
+    def __post_init__(self):
+        k0 = self.k[0]
+        self.n_ctx = len(self.k)
+        self.n_kv_heads, _, self.head_dim = k0.shape
+        self.dtype = _dtype_code(k0.dtype)
+        self.lens = [int(t.shape[1]) for t in self.k]
+        for t in list(self.k) + list(self.v or []):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == k0.dtype
+            assert t.shape[0] == self.n_kv_heads and t.shape[2] == self.head_dim
+        self._len = (ctypes.c_int32 * self.n_ctx)(*self.lens)
+        self._k = (ctypes.c_void_p * self.n_ctx)(*[t.data_ptr() for t in self.k])
+        self._v = (ctypes.c_void_p * self.n_ctx)(*[t.data_ptr() for t in self.v]) if self.v is not None else None
+        self.c = _Caches(self.n_ctx, self.n_q_heads, self.n_kv_heads, self.head_dim, self.dtype,
+                         ctypes.cast(self._len, ctypes.POINTER(ctypes.c_int32)),
+                         ctypes.cast(self._k, ctypes.POINTER(ctypes.c_void_p)),
+                         ctypes.cast(self._v, ctypes.POINTER(ctypes.c_void_p)) if self._v is not None else None)
+
+    @property
+    def total_len(self) -> int:
+        return sum(self.lens)
+
+
+def samkv_kept_count(length: int, ratio: float) -> int:
+    return int(_lib.samkv_kept_count(length, ratio))
+
+
+def samkv_workspace_bytes(n_ctx: int, n_q_heads: int, n_kv_heads: int, head_dim: int, n_q_tok: int,
+                          m_total: int) -> int:
+    return int(_lib.samkv_workspace_bytes(n_ctx, n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total))
+
+
+def samkv_score(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor], scores: torch.Tensor,
+                ws: torch.Tensor) -> None:
+    """scores [Hkv, sum L] float32 <- inner products of every key with its document's personalized query."""
+    n_q_tok = int(q_tok.shape[1])
+    w_loc = int(q_loc.shape[2]) if q_loc is not None else 0
+    assert scores.dtype == torch.float32 and tuple(scores.shape) == (caches.n_kv_heads, caches.total_len)
+    _check(_lib.samkv_score(ctypes.byref(caches.c), _ptr(q_tok), n_q_tok, _ptr(q_loc), w_loc, _ptr(scores),
+                            _ptr(ws), ws.numel() * ws.element_size(), _stream()), "samkv_score")
+
+
+def samkv_topk_select(scores: torch.Tensor, caches: Caches, ratio: float, n_sink: int, n_local: int,
+                      idx: torch.Tensor, cu_k_dev: Optional[torch.Tensor], ws: Optional[torch.Tensor] = None
+                      ) -> List[int]:
+    """idx [Hkv, M] int32 <- kept positions; returns the host prefix sums cu_k (length n_ctx + 1)."""
+    cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
+    assert idx.dtype == torch.int32
+    _check(_lib.samkv_topk_select(_ptr(scores), ctypes.byref(caches.c), ratio, n_sink, n_local, _ptr(idx),
+                                  _ptr(cu_k_dev), cu_k_host, _ptr(ws),
+                                  ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
+           "samkv_topk_select")
+    return list(cu_k_host)
+
+
+def samkv_gather(caches: Caches, idx: torch.Tensor, ratio: float, k_c: torch.Tensor, v_c: torch.Tensor) -> None:
+    """k_c, v_c [Hkv, M, d] <- kept rows of every document, concatenated."""
+    assert idx.dtype == torch.int32 and k_c.dtype == caches.k[0].dtype and v_c.dtype == caches.k[0].dtype
+    _check(_lib.samkv_gather(ctypes.byref(caches.c), _ptr(idx), ratio, _ptr(k_c), _ptr(v_c), _stream()),
+           "samkv_gather")
+
+
+def samkv_recompute_attn(q_rec: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, scale: float,
+                         out: torch.Tensor, lse: torch.Tensor, ws: Optional[torch.Tensor] = None) -> None:
+    """out [Hq, M, d], lse [Hq, M] float32 <- causal attention of the kept tokens over the compacted cache."""
+    hq, m, d = q_rec.shape
+    hkv = k_c.shape[0]
+    assert k_c.shape == (hkv, m, d) and v_c.shape == (hkv, m, d) and out.dtype == lse.dtype == torch.float32
+    assert tuple(out.shape) == (hq, m, d) and tuple(lse.shape) == (hq, m)
+    _check(_lib.samkv_recompute_attn(_ptr(q_rec), _ptr(k_c), _ptr(v_c), m, hq, hkv, d, _dtype_code(q_rec.dtype),
+                                     scale, _ptr(out), _ptr(lse), _ptr(ws),
+                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
+           "samkv_recompute_attn")
+
+
+def samkv_query_attn(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, scale: float, out: torch.Tensor,
+                     lse: torch.Tensor, ws: Optional[torch.Tensor]) -> None:
+    """out [Hq, Lq, d], lse [Hq, Lq] float32 <- attention of the query tokens over the compacted cache."""
+    hq, lq, d = q_tok.shape
+    hkv, m, _ = k_c.shape
+    assert v_c.shape == k_c.shape and out.dtype == lse.dtype == torch.float32
+    assert tuple(out.shape) == (hq, lq, d) and tuple(lse.shape) == (hq, lq)
+    _check(_lib.samkv_query_attn(_ptr(q_tok), lq, _ptr(k_c), _ptr(v_c), m, hq, hkv, d, _dtype_code(q_tok.dtype),
+                                 scale, _ptr(out), _ptr(lse), _ptr(ws),
+                                 ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
+           "samkv_query_attn")
+
+
+# ------------------------------------------------------------------------------------------------
+@dataclass
+class LayerBuffers:
+    """Device buffers of one pass of the hot path over one layer (allocated once, reused)."""
+
+    scores: torch.Tensor
+    idx: torch.Tensor
+    cu_k_dev: torch.Tensor
+    k_c: torch.Tensor
+    v_c: torch.Tensor
+    rec_out: torch.Tensor
+    rec_lse: torch.Tensor
+    q_out: torch.Tensor
+    q_lse: torch.Tensor
+    ws: torch.Tensor
+    cu_k: List[int]
+
+
+def alloc_layer_buffers(caches: Caches, n_q_tok: int, ratio: float) -> LayerBuffers:
+    dev = caches.k[0].device
+    ks = [samkv_kept_count(L, ratio) for L in caches.lens]
+    m = sum(ks)
+    hq, hkv, d = caches.n_q_heads, caches.n_kv_heads, caches.head_dim
+    dt = caches.k[0].dtype
+    ws_bytes = samkv_workspace_bytes(caches.n_ctx, hq, hkv, d, n_q_tok, m)
+    f32 = dict(device=dev, dtype=torch.float32)
+    return LayerBuffers(
+        scores=torch.empty((hkv, caches.total_len), **f32),
+        idx=torch.empty((hkv, m), device=dev, dtype=torch.int32),
+        cu_k_dev=torch.empty((caches.n_ctx + 1,), device=dev, dtype=torch.int32),
+        k_c=torch.empty((hkv, m, d), device=dev, dtype=dt), v_c=torch.empty((hkv, m, d), device=dev, dtype=dt),
+        rec_out=torch.empty((hq, m, d), **f32), rec_lse=torch.empty((hq, m), **f32),
+        q_out=torch.empty((hq, n_q_tok, d), **f32), q_lse=torch.empty((hq, n_q_tok), **f32),
+        ws=torch.empty((ws_bytes,), device=dev, dtype=torch.uint8),
+        cu_k=[0] + list(__import__("itertools").accumulate(ks)),
+    )
+
+
+def hot_path(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor], q_rec: torch.Tensor,
+             ratio: float, scale: float, buf: LayerBuffers, n_sink: int = 0, n_local: int = 0) -> None:
+    """One pass of the whole hot path of a layer: score, select, gather, recompute, query attention."""
+    samkv_score(caches, q_tok, q_loc, buf.scores, buf.ws)
+    samkv_topk_select(buf.scores, caches, ratio, n_sink, n_local, buf.idx, buf.cu_k_dev, buf.ws)
+    samkv_gather(caches, buf.idx, ratio, buf.k_c, buf.v_c)
+    samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws)
+    samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws)

@@ -1,0 +1,109 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header declares, computes the
+kept counts like the oracle and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import samkv_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "samkv.h")
+
+
+@pytest.fixture(scope="module")
+def S():
+    lib = os.path.join(ROOT, "paper_2508_11661_amd", "lib", "libsamkv.so")
+    if not os.path.exists(lib):
+        from paper_2508_11661_amd import build
+        build.build_library(verbose=False)
+    from paper_2508_11661_amd import samkv
+    return samkv
+
+
+def test_library_exports_every_declared_symbol(S):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(samkv_[a-z_]+)\s*\(", text))
+    assert declared == set(S.EXPORTS)
+    for name in declared:
+        assert hasattr(S._lib, name), name
+
+
+def test_kept_count_matches_oracle_definition(S):
+    rng = np.random.default_rng(0)
+    cases = [(L, r) for L in (1, 2, 7, 20, 40, 100, 256, 1024, 2048, 4096, 65536)
+             for r in (0.01, 0.05, 0.1, 0.15, 0.2, 0.25, 0.3, 0.5, 0.75, 1.0)]
+    cases += [(int(rng.integers(1, 65537)), float(rng.uniform(0.001, 1.0))) for _ in range(2000)]
+    for L, r in cases:
+        assert S.samkv_kept_count(L, r) == O.kept_count(L, r), (L, r)
+    assert [S.samkv_kept_count(L, 0.15) for L in (256, 1024, 2048, 4096)] == [39, 154, 308, 615]
+    assert S.samkv_kept_count(0, 0.5) == 0 and S.samkv_kept_count(10, 0.0) == 0 and S.samkv_kept_count(10, 1.5) == 0
+
+
+def test_workspace_bytes(S):
+    assert S.samkv_workspace_bytes(10, 32, 8, 128, 32, 1540) > 0
+    assert S.samkv_workspace_bytes(0, 32, 8, 128, 32, 1540) == 0
+
+
+def _caches(S, n_ctx=2, hq=4, hkv=2, d=128, dtype=1, lens=(8, 8), k=True, v=True):
+    fake = 0x1000  # never dereferenced: every call below must fail validation before any launch
+    arr_len = (ctypes.c_int32 * n_ctx)(*lens[:n_ctx])
+    arr_k = (ctypes.c_void_p * n_ctx)(*([fake] * n_ctx))
+    c = S._Caches(n_ctx, hq, hkv, d, dtype, ctypes.cast(arr_len, ctypes.POINTER(ctypes.c_int32)),
+                  ctypes.cast(arr_k, ctypes.POINTER(ctypes.c_void_p)) if k else None,
+                  ctypes.cast(arr_k, ctypes.POINTER(ctypes.c_void_p)) if v else None)
+    c._keep = (arr_len, arr_k)
+    return c
+
+
+def test_argument_errors_are_reported_before_any_launch(S):
+    L = S._lib
+    fake = ctypes.c_void_p(0x1000)
+    ok = _caches(S)
+    cu = (ctypes.c_int32 * 3)()
+    # samkv_score
+    assert L.samkv_score(None, fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(ok), None, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(ok), fake, 0, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(ok), fake, 4, None, 0, fake, None, 0, None) == -3
+    assert L.samkv_score(ctypes.byref(ok), fake, 4, None, 0, fake, fake, 16, None) == -3
+    assert L.samkv_score(ctypes.byref(_caches(S, hq=3)), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(_caches(S, d=96)), fake, 4, None, 0, fake, fake, 1 << 20, None) == -2
+    assert L.samkv_score(ctypes.byref(_caches(S, dtype=7)), fake, 4, None, 0, fake, fake, 1 << 20, None) == -2
+    assert L.samkv_score(ctypes.byref(_caches(S, lens=(8, 0))), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(_caches(S, lens=(8, 70000))), fake, 4, None, 0, fake, fake, 1 << 20, None) == -2
+    assert L.samkv_score(ctypes.byref(_caches(S, k=False)), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    # samkv_topk_select
+    assert L.samkv_topk_select(None, ctypes.byref(ok), 0.5, 0, 0, fake, None, cu, None, 0, None) == -1
+    assert L.samkv_topk_select(fake, ctypes.byref(ok), 0.0, 0, 0, fake, None, cu, None, 0, None) == -1
+    assert L.samkv_topk_select(fake, ctypes.byref(ok), 1.5, 0, 0, fake, None, cu, None, 0, None) == -1
+    assert L.samkv_topk_select(fake, ctypes.byref(ok), float("nan"), 0, 0, fake, None, cu, None, 0, None) == -1
+    assert L.samkv_topk_select(fake, ctypes.byref(ok), 0.5, 3, 2, fake, None, cu, None, 0, None) == -1   # 5 forced > k = 4
+    assert L.samkv_topk_select(fake, ctypes.byref(ok), 0.5, -1, 0, fake, None, cu, None, 0, None) == -1
+    # samkv_gather
+    assert L.samkv_gather(ctypes.byref(_caches(S, v=False)), fake, 0.5, fake, fake, None) == -1
+    assert L.samkv_gather(ctypes.byref(ok), None, 0.5, fake, fake, None) == -1
+    assert L.samkv_gather(ctypes.byref(ok), fake, 2.0, fake, fake, None) == -1
+    # attention
+    assert L.samkv_recompute_attn(None, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, fake, 0, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 3, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 100, 1, 0.1, fake, fake, None, 0, None) == -2
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 5, 0.1, fake, fake, None, 0, None) == -2
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.0, fake, fake, None, 0, None) == -1
+    assert L.samkv_query_attn(fake, 4, fake, fake, 4096, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
+    assert L.samkv_query_attn(fake, 0, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    assert S._lib.samkv_strerror(-3).decode().startswith("workspace")
+
+
+def test_binding_refuses_to_run_without_library(tmp_path, monkeypatch):
+    # the product path has no fallback: a missing library is an import error
+    import importlib
+    import paper_2508_11661_amd.samkv as mod
+    monkeypatch.setattr(mod, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        mod._load()
+    importlib.reload(mod)

@@ -1,0 +1,214 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element.
+
+Each stage is fed the ORACLE's output of the previous stage, so no expected value and no oracle
+input ever comes from the HIP path; one chained run per workload then checks the five calls
+back to back."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import samkv_oracle as O
+from paper_2508_11661_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def S():
+    from paper_2508_11661_amd import samkv
+    return samkv
+
+
+def _ws(S, x, n_rows_q, m):
+    import torch
+    w = x.workload
+    nbytes = S.samkv_workspace_bytes(len(x.k), w.n_q_heads, w.n_kv_heads, w.head_dim, n_rows_q, m)
+    return torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+
+
+def _stages(S, x, ratio, n_sink=0, n_local=0, use_bias=True, q_rec_seed_rows=None):
+    """Runs every stage on the GPU from the oracle's previous stage and checks it."""
+    import torch
+    w = x.workload
+    dt = w.dtype
+    ref = H.oracle_front(x, ratio, n_sink, n_local, use_bias)
+    m = int(ref.cu_k[-1])
+    caches = H.upload_caches(x)
+    q_tok = H.to_dev(x.q_tok, dt)
+    q_loc = H.to_dev(x.q_loc, dt) if use_bias else None
+    ws = _ws(S, x, w.n_q_tok, m)
+    hkv, hq, d = w.n_kv_heads, w.n_q_heads, w.head_dim
+
+    # ---- score
+    scores = torch.full((hkv, caches.total_len), float("nan"), device="cuda")
+    S.samkv_score(caches, q_tok, q_loc, scores, ws)
+    sg = scores.cpu().numpy().astype(np.float64)
+    bound = H.score_error_bound(x, ref)
+    cu = np.concatenate([[0], np.cumsum(x.lens)])
+    for i in range(len(x.k)):
+        err = np.abs(sg[:, cu[i]:cu[i + 1]] - ref.scores[i])
+        assert np.all(err <= bound[i]), f"score document {i}: max err {err.max():.3e}"
+
+    # ---- select (on the GPU's own float32 scores; compared under the tie-margin rule)
+    idx = torch.full((hkv, m), -1, dtype=torch.int32, device="cuda")
+    cu_k_dev = torch.zeros((len(x.k) + 1,), dtype=torch.int32, device="cuda")
+    cu_k = S.samkv_topk_select(scores, caches, ratio, n_sink, n_local, idx, cu_k_dev, ws)
+    assert cu_k == ref.cu_k.tolist() and cu_k_dev.cpu().tolist() == cu_k
+    in_margin, clean_heads = H.compare_kept_sets(idx.cpu().numpy(), ref, n_sink, n_local)
+
+    # ---- select again on the oracle's scores rounded to float32: bit-exact against the oracle's
+    #      selection of those same float32 values
+    s32 = [s.astype(np.float32) for s in ref.scores]
+    idx32, _ = O.select([s.astype(np.float64) for s in s32], ratio, n_sink, n_local)
+    scores2 = torch.from_numpy(np.concatenate(s32, axis=1)).cuda()
+    idx2 = torch.full((hkv, m), -1, dtype=torch.int32, device="cuda")
+    S.samkv_topk_select(scores2, caches, ratio, n_sink, n_local, idx2, None, ws)
+    assert np.array_equal(idx2.cpu().numpy(), idx32)
+
+    # ---- gather from the oracle's kept sets: bit-exact
+    idx_ref = torch.from_numpy(ref.idx).cuda()
+    k_c = torch.zeros((hkv, m, d), dtype=H.torch_dtype(dt), device="cuda")
+    v_c = torch.zeros_like(k_c)
+    S.samkv_gather(caches, idx_ref, ratio, k_c, v_c)
+    assert np.array_equal(k_c.float().cpu().numpy(), ref.k_c)
+    assert np.array_equal(v_c.float().cpu().numpy(), ref.v_c)
+
+    # ---- attention over the oracle's compacted cache
+    scale = 1.0 / math.sqrt(d)
+    q_rec_np = synth.make_q_rec(w, x.layer, m)
+    q_rec = H.to_dev(q_rec_np, dt)
+    kc_ref, vc_ref = H.to_dev(ref.k_c, dt), H.to_dev(ref.v_c, dt)
+    out = torch.full((hq, m, d), float("nan"), device="cuda")
+    lse = torch.full((hq, m), float("nan"), device="cuda")
+    S.samkv_recompute_attn(q_rec, kc_ref, vc_ref, scale, out, lse, ws)
+    o_ref, l_ref = O.attention(q_rec_np, ref.k_c, ref.v_c, scale, True)
+    e_rec = H.check_attention(out.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, dt, "recompute")
+
+    out_q = torch.full((hq, w.n_q_tok, d), float("nan"), device="cuda")
+    lse_q = torch.full((hq, w.n_q_tok), float("nan"), device="cuda")
+    S.samkv_query_attn(q_tok, kc_ref, vc_ref, scale, out_q, lse_q, ws)
+    oq_ref, lq_ref = O.attention(x.q_tok, ref.k_c, ref.v_c, scale, False)
+    e_q = H.check_attention(out_q.cpu().numpy(), lse_q.cpu().numpy(), oq_ref, lq_ref, dt, "query")
+
+    # ---- the five calls chained on the GPU; heads whose kept set equals the oracle's are compared end to end
+    buf = S.alloc_layer_buffers(caches, w.n_q_tok, ratio)
+    S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf, n_sink, n_local)
+    torch.cuda.synchronize()
+    G = hq // hkv
+    heads = [h for h in range(hq) if h // G in clean_heads]
+    assert heads, "no KV head reproduced the oracle's kept set exactly"
+    H.check_attention(buf.rec_out.cpu().numpy()[heads], buf.rec_lse.cpu().numpy()[heads], o_ref[heads], l_ref[heads],
+                      dt, "chained recompute")
+    H.check_attention(buf.q_out.cpu().numpy()[heads], buf.q_lse.cpu().numpy()[heads], oq_ref[heads], lq_ref[heads],
+                      dt, "chained query")
+    return dict(in_margin=in_margin, clean=len(clean_heads), e_rec=e_rec, e_q=e_q, m=m)
+
+
+def test_config1_tiny_f32(S):
+    r = _stages(S, synth.make_layer(synth.WORKLOADS["tiny_f32"]), 0.15)
+    assert r["m"] == 156
+
+
+def test_config2_llama_layer_bf16(S):
+    r = _stages(S, synth.make_layer(synth.WORKLOADS["llama3_8b_layer"]), 0.15)
+    assert r["m"] == 1540
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_ragged_documents_with_forced_positions(S, dtype, d):
+    # lengths off every tile size; M = 90 + 24 + 308 + 154 = 576 kept rows; initial/local positions forced
+    x = synth.make_small(11, dtype, [300, 77, 1025, 513], 8, 2, d, 5, 7)
+    _stages(S, x, 0.3, n_sink=4, n_local=8)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_full_budget_is_dense_attention(S, dtype):
+    # budget 100 %: every token kept, compacted cache = concatenation, query attention = dense attention
+    x = synth.make_small(12, dtype, [130, 65, 200], 4, 4, 128, 9, 3)
+    r = _stages(S, x, 1.0)
+    assert r["m"] == 395 and r["in_margin"] == 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_single_document_and_no_local_cache(S, dtype):
+    x = synth.make_small(13, dtype, [333], 4, 1, 64, 3, 2, dup=0.0)
+    _stages(S, x, 0.2)
+    x = synth.make_small(14, dtype, [100, 90], 2, 2, 128, 1, 1)
+    _stages(S, x, 0.5, use_bias=False)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_degenerate_sizes(S, dtype):
+    # documents of one and two tokens, compacted cache of a handful of rows
+    x = synth.make_small(15, dtype, [1, 2, 1], 2, 1, 64, 1, 1, planted=0.0, dup=0.0)
+    r = _stages(S, x, 0.15)
+    assert r["m"] == 3
+    x = synth.make_small(16, dtype, [1], 1, 1, 128, 2, 1, planted=0.0, dup=0.0)
+    assert _stages(S, x, 1.0)["m"] == 1
+
+
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 1000, 1024, 1025, 4096, 4097, 16384, 20000, 65536])
+def test_select_alone_exact_with_ties(S, L):
+    """Selection in isolation on float32 scores with many exact ties (quantised values): bit-exact."""
+    import torch
+    rng = np.random.default_rng(L)
+    hkv = 2
+    lens = [L, max(1, L // 3)]
+    rows = [np.round(rng.standard_normal((hkv, n)) * 4.0).astype(np.float32) / 4.0 for n in lens]
+    rows[0][0, : min(L, 50)] = 0.0           # a run of equal scores at the threshold region
+    rows[0][1, :] = -1.5                       # a whole row of equal scores
+    ratio = 0.15
+    n_sink, n_local = (1, 2) if min(O.kept_count(n, ratio) for n in lens) >= 3 else (0, 0)
+    want, cu = O.select([r.astype(np.float64) for r in rows], ratio, n_sink, n_local)
+
+    # select reads no K/V: uninitialised caches of the right shape carry the lengths
+    k = [torch.empty((hkv, n, 64), dtype=torch.bfloat16, device="cuda") for n in lens]
+    caches = S.Caches(k, None, hkv)
+    scores = torch.from_numpy(np.concatenate(rows, axis=1)).cuda()
+    idx = torch.full((hkv, int(cu[-1])), -1, dtype=torch.int32, device="cuda")
+    got_cu = S.samkv_topk_select(scores, caches, ratio, n_sink, n_local, idx, None, None)
+    assert got_cu == cu.tolist()
+    assert np.array_equal(idx.cpu().numpy(), want)
+    # negative zero, infinities and denormals keep their numeric order
+    special = np.array([[-0.0, 0.0, np.inf, -np.inf, 1e-40, -1e-40, 3.0, -3.0]], dtype=np.float32)
+    k = [torch.empty((1, 8, 64), dtype=torch.bfloat16, device="cuda")]
+    caches = S.Caches(k, None, 1)
+    idx = torch.full((1, 4), -1, dtype=torch.int32, device="cuda")
+    S.samkv_topk_select(torch.from_numpy(special).cuda(), caches, 0.5, 0, 0, idx, None, None)
+    assert idx.cpu().numpy().tolist() == [[0, 2, 4, 6]]
+
+
+def test_gather_clamps_out_of_range_indices(S):
+    import torch
+    x = synth.make_small(17, "bf16", [40, 50], 2, 2, 128, 2, 2)
+    caches = H.upload_caches(x)
+    ratio = 0.1
+    m = sum(O.kept_count(n, ratio) for n in x.lens)
+    idx = torch.tensor([[-5, 0, 10, 39, 0, 49, 1000, 7, 8]] * 2, dtype=torch.int32, device="cuda")
+    assert idx.shape[1] == m
+    k_c = torch.zeros((2, m, 128), dtype=torch.bfloat16, device="cuda")
+    v_c = torch.zeros_like(k_c)
+    S.samkv_gather(caches, idx, ratio, k_c, v_c)
+    clamped = np.array([0, 0, 10, 39, 0, 49, 49, 7, 8])
+    want = np.stack([np.concatenate([x.k[0][g, clamped[:4]], x.k[1][g, clamped[4:]]]) for g in range(2)])
+    assert np.array_equal(k_c.float().cpu().numpy(), want)
+
+
+def test_outputs_are_deterministic(S):
+    import torch
+    x = synth.make_layer(synth.WORKLOADS["llama3_8b_layer"])
+    w = x.workload
+    caches = H.upload_caches(x)
+    q_tok, q_loc = H.to_dev(x.q_tok, w.dtype), H.to_dev(x.q_loc, w.dtype)
+    m = sum(S.samkv_kept_count(n, 0.15) for n in x.lens)
+    q_rec = H.to_dev(synth.make_q_rec(w, 0, m), w.dtype)
+    runs = []
+    for _ in range(2):
+        buf = S.alloc_layer_buffers(caches, w.n_q_tok, 0.15)
+        S.hot_path(caches, q_tok, q_loc, q_rec, 0.15, 1.0 / math.sqrt(w.head_dim), buf)
+        torch.cuda.synchronize()
+        runs.append([t.clone() for t in (buf.scores, buf.idx, buf.k_c, buf.rec_out, buf.q_out, buf.q_lse)])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
