@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the SamKV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--ratio R]
+
+A step is one pass of the whole hot path (samkv_score, samkv_topk_select, samkv_gather,
+samkv_recompute_attn, samkv_query_attn) over the per-document caches of one layer (for the
+32-layer workload: over all 32 layers).  Inputs are seeded synthetic caches already resident in
+HBM; enough distinct copies are rotated that the working set exceeds twice the 256 MB Infinity
+Cache, so K is streamed from HBM and not from cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
+FP32_VALU_PEAK_TFLOPS = 157.3
+KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")
+
+
+def algorithmic_work(w, lens, m, n_q_tok):
+    """Algorithmic bytes / flops of one pass over one layer (what the method itself must move or compute)."""
+    e = 2 if w.dtype == "bf16" else 4
+    tot, hkv, hq, d = sum(lens), w.n_kv_heads, w.n_q_heads, w.head_dim
+    return {
+        "score": {"bytes": tot * hkv * (d * e + 4), "flops": 2 * d * tot * hkv},
+        "select": {"bytes": tot * hkv * 4 + m * hkv * 4, "flops": 0},
+        "gather": {"bytes": m * hkv * (4 * d * e + 4), "flops": 0},
+        "recompute_attn": {"bytes": (2 * hq + 2 * hkv) * m * d * e + hq * m * (d + 1) * 4,
+                           "flops": 4 * hq * d * m * (m + 1) // 2},
+        "query_attn": {"bytes": 2 * m * hkv * d * e + hq * n_q_tok * (d * e + (d + 1) * 4),
+                       "flops": 4 * hq * d * n_q_tok * m},
+    }
+
+
+def read_traffic(kernel_file: str):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (or None)."""
+    path = os.path.join(ROOT, "profiles", kernel_file)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
+    """Times the fp64 oracle (as it stands) on the host over the same layer; attention rows are sampled
+    when the full computation would not fit the time budget, and extrapolated by pair count."""
+    import numpy as np
+    from oracle import samkv_oracle as O
+    from paper_2508_11661_amd import synth
+
+    w = layer.workload
+    t0, c0 = time.perf_counter(), time.process_time()
+    n = len(layer.k)
+    q_hat = O.personalized_query(layer.q_tok, layer.q_loc, n)
+    scores = O.score(q_hat, layer.k)
+    idx, cu_k = O.select(scores, ratio)
+    k_c, v_c = O.gather(layer.k, layer.v, idx, cu_k)
+    t_front = time.perf_counter() - t0
+    m = int(cu_k[-1])
+    scale = 1.0 / math.sqrt(w.head_dim)
+    q_rec = synth.make_q_rec(w, layer.layer, m)
+    rng = np.random.default_rng(0)
+    if n_sample_rows >= m:
+        rows, frac = None, 1.0
+    else:
+        rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, size=n_sample_rows - 2)]))
+        frac = float((rows + 1).sum()) / (m * (m + 1) / 2)
+    t1 = time.perf_counter()
+    O.attention(q_rec, k_c, v_c, scale, True, rows=rows)
+    t_rec = (time.perf_counter() - t1) / frac
+    t2 = time.perf_counter()
+    O.attention(layer.q_tok, k_c, v_c, scale, False)
+    t_q = time.perf_counter() - t2
+    wall = time.perf_counter() - t0
+    cores = max(1, round((time.process_time() - c0) / wall))
+    total = t_front + t_rec + t_q
+    sample = ("whole layer, every step of the path" if rows is None else
+              f"score/select/gather/query attention in full; recompute attention on {len(rows)} of {m} rows per "
+              f"head ({frac:.3%} of the causal pairs), time extrapolated by pair count")
+    return {"value": sum(layer.lens) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": sample, "seconds_measured": round(wall, 2), "ms_per_step_extrapolated": round(total * 1e3, 1)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama3_8b_layer")
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="layers of a multi-layer workload to run (default all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2508_11661_amd import samkv, synth
+    from tests.helpers import to_dev
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    w = synth.WORKLOADS[args.workload]
+    ratio = args.ratio if args.ratio is not None else (0.15 if 0.15 in w.ratios else w.ratios[0])
+    n_layers = args.layers or w.n_layers
+    e = 2 if w.dtype == "bf16" else 4
+    scale = 1.0 / math.sqrt(w.head_dim)
+
+    # ---- inputs: n_layers layers, replicated until the K/V working set passes 512 MB
+    layers_np = [synth.make_layer(w, l) for l in range(n_layers)]
+    m = sum(samkv.samkv_kept_count(n, ratio) for n in w.lens)
+    kv_bytes = 2 * sum(w.lens) * w.n_kv_heads * w.head_dim * e * n_layers
+    n_rot = max(1, min(16, math.ceil(512e6 / kv_bytes)))
+    sets = []
+    for rot in range(n_rot):
+        for l, x in enumerate(layers_np):
+            k = [to_dev(a, w.dtype) for a in x.k]
+            v = [to_dev(a, w.dtype) for a in x.v]
+            sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads), q_tok=to_dev(x.q_tok, w.dtype),
+                             q_loc=to_dev(x.q_loc, w.dtype),
+                             q_rec=to_dev(synth.make_q_rec(w, l, m), w.dtype)))
+    buf = samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio)
+    torch.cuda.synchronize()
+
+    calls = {
+        "score": lambda s: samkv.samkv_score(s["caches"], s["q_tok"], s["q_loc"], buf.scores, buf.ws),
+        "select": lambda s: samkv.samkv_topk_select(buf.scores, s["caches"], ratio, 0, 0, buf.idx, buf.cu_k_dev, buf.ws),
+        "gather": lambda s: samkv.samkv_gather(s["caches"], buf.idx, ratio, buf.k_c, buf.v_c),
+        "recompute_attn": lambda s: samkv.samkv_recompute_attn(s["q_rec"], buf.k_c, buf.v_c, scale, buf.rec_out,
+                                                               buf.rec_lse, buf.ws),
+        "query_attn": lambda s: samkv.samkv_query_attn(s["q_tok"], buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws),
+    }
+
+    def step(i, events=None):
+        for l in range(n_layers):
+            s = sets[(i * n_layers + l) % len(sets)]
+            for name in KERNELS:
+                if events is not None:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    calls[name](s)
+                    b.record()
+                    events[name].append((a, b))
+                else:
+                    calls[name](s)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = {name: [] for name in KERNELS}
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    work = algorithmic_work(w, w.lens, m, w.n_q_tok)
+    per_kernel = {}
+    for name in KERNELS:
+        ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
+        gbs = work[name]["bytes"] / (ms * 1e-3) / 1e9
+        tfl = work[name]["flops"] / (ms * 1e-3) / 1e12
+        per_kernel[name] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
+                            "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+        if name.endswith("attn"):
+            peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+            per_kernel[name]["frac_compute"] = round(tfl / peak, 4)
+
+    dom = max(KERNELS, key=lambda n: per_kernel[n]["ms"])
+    if dom.endswith("attn") and w.dtype == "bf16":
+        roof = {"kernel": dom, "bound": "mfma", "achieved": per_kernel[dom]["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS, 4)}
+    elif dom.endswith("attn"):
+        roof = {"kernel": dom, "bound": "alu", "achieved": per_kernel[dom]["TFLOP/s"], "peak": FP32_VALU_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / FP32_VALU_PEAK_TFLOPS, 4)}
+    else:
+        roof = {"kernel": dom, "bound": "hbm", "achieved": per_kernel[dom]["GB/s"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(per_kernel[dom]["GB/s"] / HBM_PEAK_GBS, 4)}
+    roof["avg_launch_ms"] = per_kernel[dom]["ms"]
+    roof["traffic"] = read_traffic(f"{dom}_{w.name}.pmc.txt")
+
+    out = {
+        "metric": "KV tokens scored per second through the whole sparse-prefill hot path "
+                  "(score+select+gather+recompute_attn+query_attn)",
+        "value": round(sum(w.lens) * n_layers / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_layer": round(ms_per_step / n_layers, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n_layers": n_layers, "n_ctx": w.n_ctx, "ctx_len": w.ctx_len,
+                   "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "n_q_tok": w.n_q_tok, "budget_ratio": ratio, "kept_per_ctx": m // w.n_ctx, "m_total": m,
+                   "input_copies_rotated": n_rot},
+        "per_kernel": per_kernel,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        rows = args.cpu_sample_rows or (m if m <= 2048 else 48)
+        out["cpu_baseline"] = cpu_baseline(layers_np[0], ratio, rows)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
