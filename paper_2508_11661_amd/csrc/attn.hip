@@ -60,10 +60,16 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int rw = lane & 31, h = lane >> 5;
-  const int qt = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;  // long causal tiles first
+  // grid = (batch, row tile, key chunk).  Workgroups are handed out x-fastest and round-robin over the 8
+  // XCDs, so (1) every batch's longest causal row tiles start first and the short ones fill the tail,
+  // and (2) blockIdx.x % n_kv picks the KV head: the query heads that share a K/V stream run on the
+  // same XCD and find its tiles in that XCD's L2.
+  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
   const int q0 = qt * C::BQ;
-  const int batch = blockIdx.y, split = blockIdx.z;
-  const int kvh = batch / a.batch_per_kv;
+  const int n_kv = a.n_batch / a.batch_per_kv;
+  const int kvh = blockIdx.x % n_kv;
+  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
+  const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + C::BQ) : min(a.m, kv_begin + a.chunk);
   const int n_tiles = (kv_end - kv_begin + C::BK - 1) / C::BK;
@@ -116,6 +122,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
 
   load_tile(0);
   store_tile(0);
+  // Drain every outstanding load (the query fragment included) before the loop: otherwise the loop's
+  // first use of the query registers has to be guarded by waits that also cover the next tile's prefetch.
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   for (int tile = 0; tile < n_tiles; ++tile) {
@@ -128,14 +137,23 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
       const char* sk = smem + (tile & 1) * C::TILE_BYTES;
       const char* sv = sk + C::BK * C::KSTR;
       f32x16 s[2];
+      {
+        // all K fragments of the tile are requested before the first product, so the LDS latency is
+        // paid once per tile instead of once per instruction
+        bf16x8 ak[2][ND];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+          for (int dc = 0; dc < ND; ++dc)
+            ak[kb][dc] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + rw) * C::KSTR + dc * 32 + h * 16);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int dc = 0; dc < ND; ++dc) {
-          const bf16x8 ak = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + rw) * C::KSTR + dc * 32 + h * 16);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[dc], s[kb], 0, 0, 0);
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+#pragma unroll
+          for (int dc = 0; dc < ND; ++dc)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[kb][dc], bq[dc], s[kb], 0, 0, 0);
         }
       }
       // accumulator register j of block kb holds key k0 + kb*32 + 8*(j/4) + 4*h + (j%4) for row r
@@ -237,10 +255,12 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
   __shared__ float sP[RB * BK];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int kx = lane & 31, ch = lane >> 5;
-  const int qt = CAUSAL ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
   const int q0 = qt * RB;
-  const int batch = blockIdx.y, split = blockIdx.z;
-  const int kvh = batch / a.batch_per_kv;
+  const int n_kv = a.n_batch / a.batch_per_kv;
+  const int kvh = blockIdx.x % n_kv;
+  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
+  const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + RB) : min(a.m, kv_begin + a.chunk);
   const int n_tiles = (kv_end - kv_begin + BK - 1) / BK;
@@ -376,7 +396,7 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
     attr_set = true;
   }
   AttnArgs a = make_args(l);
-  dim3 grid((l.rows + C::BQ - 1) / C::BQ, l.n_batch, a.n_split);
+  dim3 grid(l.n_batch, (l.rows + C::BQ - 1) / C::BQ, a.n_split);
   hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL>), grid, dim3(256), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
@@ -384,7 +404,7 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
 template <int D, bool CAUSAL>
 hipError_t run_f32(const AttnLaunch& l, hipStream_t s) {
   AttnArgs a = make_args(l);
-  dim3 grid((l.rows + 15) / 16, l.n_batch, a.n_split);
+  dim3 grid(l.n_batch, (l.rows + 15) / 16, a.n_split);
   hipLaunchKernelGGL((k_attn_f32<D, CAUSAL>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }

@@ -48,6 +48,7 @@ struct ScoreLaunch {
   float* ws_que;    // [Hq][d]
   float* ws_loc;    // [N][Hq][d]
   float* ws_w;      // [N][Hq]
+  float* ws_base;   // [Hq][d]  sum over all documents of |cos| * Q_loc
   float* ws_qt;     // [N][Hkv][d]
 };
 hipError_t launch_score(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s);
@@ -61,7 +62,7 @@ struct SelectLaunch {
 hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s);
 
 struct GatherLaunch {
-  int n_ctx, hkv, row_bytes, m_total;
+  int n_ctx, hkv, row_bytes, m_total, max_k;
   const int32_t* idx;
   void* k_c;
   void* v_c;

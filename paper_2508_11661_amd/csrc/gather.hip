@@ -4,44 +4,51 @@
 // head, plus the 4-byte index.
 //
 // A row is LPR 16-byte chunks; LPR lanes copy one K row and one V row, a wave copies 64/LPR rows per
-// step and runs STEPS steps with all of its loads issued before the first store.
+// step and runs STEPS steps with all of its loads issued before the first store.  The grid is
+// (row chunk, document, KV head), so the document's base pointers are uniform over a workgroup.
 #include "common.hpp"
 
 namespace samkv {
 namespace {
 
 template <int ROW_BYTES>
-__global__ __launch_bounds__(256) void k_gather(PtrTable kt, PtrTable vt, IntTable cu_len, IntTable cu_k, int n_ctx,
-                                                int m_total, const int32_t* idx, char* k_c, char* v_c) {
+__global__ __launch_bounds__(256) void k_gather(PtrTable kt, PtrTable vt, IntTable cu_len, IntTable cu_k, int m_total,
+                                                const int32_t* idx, char* k_c, char* v_c) {
   constexpr int LPR = ROW_BYTES / 16;
   constexpr int RPS = 64 / LPR;  // rows per wave step
-  constexpr int STEPS = 4;
+  constexpr int STEPS = 8;
   constexpr int ROWS_PER_BLOCK = RPS * STEPS * 4;
-  const int g = blockIdx.y;
+  const int i = blockIdx.y, g = blockIdx.z;  // document and KV head are uniform over the block
+  const int k_i = cu_k.v[i + 1] - cu_k.v[i];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rg = lane / LPR;
-  const int m0 = blockIdx.x * ROWS_PER_BLOCK + wave * (RPS * STEPS);
+  const int r0 = blockIdx.x * ROWS_PER_BLOCK + wave * (RPS * STEPS);
+  if (r0 >= k_i) return;
+  const int L = cu_len.v[i + 1] - cu_len.v[i];
+  const char* ksrc = static_cast<const char*>(kt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
+  const char* vsrc = static_cast<const char*>(vt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
+  const size_t out0 = ((size_t)g * m_total + cu_k.v[i]) * ROW_BYTES + sub * 16;
+  const int32_t* ip = idx + (size_t)g * m_total + cu_k.v[i];
 
+  int p[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int r = r0 + s * RPS + rg;
+    p[s] = ip[r < k_i ? r : k_i - 1];
+  }
   u32x4 xk[STEPS], xv[STEPS];
 #pragma unroll
   for (int s = 0; s < STEPS; ++s) {
-    int m = m0 + s * RPS + rg;
-    m = m < m_total ? m : m_total - 1;
-    const int i = find_ctx(cu_k, n_ctx, m);
-    const int L = cu_len.v[i + 1] - cu_len.v[i];
-    int p = idx[(size_t)g * m_total + m];
-    p = p < 0 ? 0 : (p >= L ? L - 1 : p);
-    const size_t off = ((size_t)g * L + p) * ROW_BYTES + sub * 16;
-    xk[s] = *reinterpret_cast<const u32x4*>(static_cast<const char*>(kt.p[i]) + off);
-    xv[s] = *reinterpret_cast<const u32x4*>(static_cast<const char*>(vt.p[i]) + off);
+    const int q = p[s] < 0 ? 0 : (p[s] >= L ? L - 1 : p[s]);
+    xk[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ksrc + (size_t)q * ROW_BYTES));
+    xv[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vsrc + (size_t)q * ROW_BYTES));
   }
 #pragma unroll
   for (int s = 0; s < STEPS; ++s) {
-    const int m = m0 + s * RPS + rg;
-    if (m < m_total) {
-      const size_t off = ((size_t)g * m_total + m) * ROW_BYTES + sub * 16;
-      __builtin_nontemporal_store(xk[s], reinterpret_cast<u32x4*>(k_c + off));
-      __builtin_nontemporal_store(xv[s], reinterpret_cast<u32x4*>(v_c + off));
+    const int r = r0 + s * RPS + rg;
+    if (r < k_i) {
+      __builtin_nontemporal_store(xk[s], reinterpret_cast<u32x4*>(k_c + out0 + (size_t)r * ROW_BYTES));
+      __builtin_nontemporal_store(xv[s], reinterpret_cast<u32x4*>(v_c + out0 + (size_t)r * ROW_BYTES));
     }
   }
 }
@@ -49,9 +56,9 @@ __global__ __launch_bounds__(256) void k_gather(PtrTable kt, PtrTable vt, IntTab
 template <int ROW_BYTES>
 hipError_t run(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
                const IntTable& cu_k, hipStream_t s) {
-  constexpr int ROWS_PER_BLOCK = (64 / (ROW_BYTES / 16)) * 4 * 4;
-  dim3 grid((a.m_total + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, a.hkv);
-  hipLaunchKernelGGL((k_gather<ROW_BYTES>), grid, dim3(256), 0, s, k, v, cu_len, cu_k, a.n_ctx, a.m_total, a.idx,
+  constexpr int ROWS_PER_BLOCK = (64 / (ROW_BYTES / 16)) * 8 * 4;
+  dim3 grid((a.max_k + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, a.n_ctx, a.hkv);
+  hipLaunchKernelGGL((k_gather<ROW_BYTES>), grid, dim3(256), 0, s, k, v, cu_len, cu_k, a.m_total, a.idx,
                      static_cast<char*>(a.k_c), static_cast<char*>(a.v_c));
   return hipGetLastError();
 }

@@ -62,14 +62,16 @@ int kept_table(const samkv_caches* c, float ratio, int n_sink, int n_local, IntT
   return SAMKV_OK;
 }
 
-// Score workspace: Q_que [Hq][d], Q_loc [N][Hq][d], |cos| [N][Hq], folded vectors [N][Hkv][d], float32.
-struct ScoreWs { size_t que, loc, w, qt, bytes; };
+// Score workspace: Q_que [Hq][d], Q_loc [N][Hq][d], |cos| [N][Hq], bias sums [Hq][d], folded vectors
+// [N][Hkv][d], all float32.
+struct ScoreWs { size_t que, loc, w, base, qt, bytes; };
 ScoreWs score_ws(int n_ctx, int hq, int hkv, int d) {
   ScoreWs w;
   size_t o = 0;
   w.que = o; o = align_up(o + (size_t)hq * d * 4);
   w.loc = o; o = align_up(o + (size_t)n_ctx * hq * d * 4);
   w.w = o;   o = align_up(o + (size_t)n_ctx * hq * 4);
+  w.base = o; o = align_up(o + (size_t)hq * d * 4);
   w.qt = o;  o = align_up(o + (size_t)n_ctx * hkv * d * 4);
   w.bytes = o;
   return w;
@@ -82,11 +84,11 @@ SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
   const int bk = dtype == SAMKV_BF16 ? 64 : 32;
   const long long base = (long long)((rows + bq - 1) / bq) * n_batch;
   const int key_tiles = (m + bk - 1) / bk;
-  long long want = (1024 + base - 1) / base;  // aim at ~4 workgroups per compute unit
-  if (want > key_tiles) want = key_tiles;
+  long long want = (512 + base - 1) / base;  // aim at ~2 workgroups per compute unit
   if (want > 64) want = 64;
   if (want < 1) want = 1;
   int tiles_per = (int)((key_tiles + want - 1) / want);
+  if (tiles_per < 4) tiles_per = 4;  // a chunk shorter than a few tiles costs more in the merge than it gains
   SplitPlan p;
   p.chunk = tiles_per * bk;
   p.n_split = (m + p.chunk - 1) / p.chunk;
@@ -108,7 +110,7 @@ int check_attn(const void* q, const void* k, const void* v, int rows, int m, int
   if (rows < 1 || m < 1 || hq < 1 || hkv < 1 || hq % hkv != 0 || !(scale > 0.f) || !isfinite(scale)) return SAMKV_EINVAL;
   if (dtype != SAMKV_F32 && dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
   if (d != 64 && d != 128) return SAMKV_EUNSUPPORTED;
-  if ((long long)hq * rows > 0x7FFFFFFF / 256 || m > 0x7FFFFFFF / 512) return SAMKV_EUNSUPPORTED;
+  if ((long long)hq * rows > 0x7FFFFFFF / 256 || m > 0x7FFFFFFF / 512 || rows / 16 > 65535) return SAMKV_EUNSUPPORTED;
   return SAMKV_OK;
 }
 
@@ -161,6 +163,7 @@ int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, 
   a.ws_que = reinterpret_cast<float*>(base + w.que);
   a.ws_loc = reinterpret_cast<float*>(base + w.loc);
   a.ws_w = reinterpret_cast<float*>(base + w.w);
+  a.ws_base = reinterpret_cast<float*>(base + w.base);
   a.ws_qt = reinterpret_cast<float*>(base + w.qt);
   return dev(launch_score(a, kt, s.cu_len, static_cast<hipStream_t>(stream)));
 }
@@ -198,6 +201,8 @@ int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, vo
   GatherLaunch a;
   a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.row_bytes = s.d * (s.dtype == SAMKV_BF16 ? 2 : 4);
   a.m_total = cu_k.v[s.n_ctx]; a.idx = idx; a.k_c = k_c; a.v_c = v_c;
+  a.max_k = 0;
+  for (int i = 0; i < s.n_ctx; ++i) a.max_k = cu_k.v[i + 1] - cu_k.v[i] > a.max_k ? cu_k.v[i + 1] - cu_k.v[i] : a.max_k;
   return dev(launch_gather(a, kt, vt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
 }
 

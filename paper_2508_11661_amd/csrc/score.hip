@@ -1,11 +1,11 @@
 // samkv_score: personalized query vectors (Sec. 3.1, Eq. 1) and the inner product of every cached key
 // with the vector of its own document (Sec. 3.2).
 //
-// Three launches on one stream:
-//   k_pool    one block per (document j, query head h): mean-pools the user query's Q rows (Q_que) and
-//             document j's local Q cache (Q_loc_j), then takes |cos(Q_que[h], Q_loc_j[h])|.
-//   k_qtilde  one block per (document i, KV head g): Eq. 1 for the query heads of the group, folded
-//             into one vector (the mean over the group is linear, so one pass over K serves all heads).
+// Four launches on one stream:
+//   k_pool    mean-pools the user query's Q rows (Q_que) and every document's local Q cache (Q_loc_j).
+//   k_bias    per query head: |cos(Q_que, Q_loc_j)| for every j and the weighted sum over all documents.
+//   k_qtilde  Eq. 1 for the query heads of a KV group, folded into one vector per document (the mean
+//             over the group is linear, so one pass over K serves all heads of the group).
 //   k_score   streams K once.  HBM-bound: d*e bytes read and 4 bytes written per token and KV head.
 #include "common.hpp"
 
@@ -73,52 +73,78 @@ __device__ void pool_rows(const void* src, int n_rows, float* red, float* dst) {
   __syncthreads();
 }
 
+// blockIdx.y == 0 pools the user query's rows of head h (Q_que); blockIdx.y == j + 1 pools document j's
+// local Q cache (Q_loc_j).  Every input row is read exactly once.
 template <bool BF16, int D>
 __global__ __launch_bounds__(256) void k_pool(const void* q_tok, int n_q_tok, const void* q_loc, int w_loc,
-                                              int hq, float* que, float* loc, float* wgt) {
+                                              int hq, float* que, float* loc) {
   constexpr int EPL = BF16 ? 8 : 4;
   constexpr int RPB = 256 / (D / EPL);
   constexpr size_t ESZ = BF16 ? 2 : 4;
   __shared__ float red[RPB * D];
-  __shared__ float s_que[D];
-  __shared__ float s_loc[D];
-  const int h = blockIdx.x, j = blockIdx.y;
-  pool_rows<BF16, D>(static_cast<const char*>(q_tok) + (size_t)h * n_q_tok * D * ESZ, n_q_tok, red, s_que);
-  if (j == 0 && threadIdx.x < D) que[h * D + threadIdx.x] = s_que[threadIdx.x];
-  if (q_loc == nullptr) return;
-  pool_rows<BF16, D>(static_cast<const char*>(q_loc) + ((size_t)j * hq + h) * w_loc * D * ESZ, w_loc, red, s_loc);
-  if (threadIdx.x < D) loc[((size_t)j * hq + h) * D + threadIdx.x] = s_loc[threadIdx.x];
-  if (threadIdx.x < 64) {
+  __shared__ float s_out[D];
+  const int h = blockIdx.x;
+  if (blockIdx.y == 0) {
+    pool_rows<BF16, D>(static_cast<const char*>(q_tok) + (size_t)h * n_q_tok * D * ESZ, n_q_tok, red, s_out);
+    if (threadIdx.x < D) que[h * D + threadIdx.x] = s_out[threadIdx.x];
+  } else {
+    const int j = blockIdx.y - 1;
+    pool_rows<BF16, D>(static_cast<const char*>(q_loc) + ((size_t)j * hq + h) * w_loc * D * ESZ, w_loc, red, s_out);
+    if (threadIdx.x < D) loc[((size_t)j * hq + h) * D + threadIdx.x] = s_out[threadIdx.x];
+  }
+}
+
+// One block per query head h.  Step 1: w_j[h] = |cos(Q_que[h], Q_loc_j[h])| for every document j (one
+// wave per j, butterfly sums).  Step 2: bias[h][c] = sum_j w_j[h] Q_loc_j[h][c]; thread (channel c,
+// slice s) adds the documents j = s, s + NS, ..., and the slices meet in LDS in a fixed order.
+__global__ __launch_bounds__(1024) void k_bias(const float* que, const float* loc, float* wgt, float* bias, int n_ctx,
+                                               int hq, int d) {
+  __shared__ float red[1024];
+  __shared__ float w_s[SAMKV_MAX_CTX];
+  const int h = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  for (int j = wave; j < n_ctx; j += 16) {
     float dot = 0.f, na = 0.f, nb = 0.f;
-    for (int c = threadIdx.x; c < D; c += 64) {
-      float a = s_que[c], b = s_loc[c];
-      dot += a * b; na += a * a; nb += b * b;
+    for (int c = lane; c < d; c += 64) {
+      const float a = que[h * d + c], b = loc[((size_t)j * hq + h) * d + c];
+      dot = fmaf(a, b, dot); na = fmaf(a, a, na); nb = fmaf(b, b, nb);
     }
     for (int off = 32; off >= 1; off >>= 1) {
       dot += __shfl_xor(dot, off);
       na += __shfl_xor(na, off);
       nb += __shfl_xor(nb, off);
     }
-    if (threadIdx.x == 0) {
-      float ra = sqrtf(na), rb = sqrtf(nb);
-      wgt[j * hq + h] = (ra < 1e-20f || rb < 1e-20f) ? 0.f : fabsf(dot / (ra * rb));
+    if (lane == 0) {
+      const float ra = sqrtf(na), rb = sqrtf(nb);
+      const float w = (ra < 1e-20f || rb < 1e-20f) ? 0.f : fabsf(dot / (ra * rb));
+      w_s[j] = w;
+      wgt[j * hq + h] = w;
     }
+  }
+  __syncthreads();
+  const int c = t % d, sl = t / d, ns = 1024 / d;
+  float acc = 0.f;
+  for (int j = sl; j < n_ctx; j += ns) acc = fmaf(w_s[j], loc[((size_t)j * hq + h) * d + c], acc);
+  red[t] = acc;
+  __syncthreads();
+  if (t < d) {
+    float b = 0.f;
+    for (int s2 = 0; s2 < ns; ++s2) b += red[s2 * d + c];
+    bias[h * d + c] = b;
   }
 }
 
-// Eq. 1 per query head, then the mean over the heads of KV group g.  One thread per channel.
-__global__ void k_qtilde(const float* que, const float* loc, const float* wgt, float* qt, int n_ctx, int hq,
-                         int hkv, int d, int with_bias) {
+// Eq. 1 for the query heads of KV group g, then their mean: the bias of document i is the sum over all
+// documents minus document i's own term.  One block per (document, KV head), one thread per channel.
+__global__ void k_qtilde(const float* que, const float* bias, const float* loc, const float* wgt, float* qt, int n_ctx,
+                         int hq, int hkv, int d, int with_bias) {
   const int i = blockIdx.x, g = blockIdx.y, c = threadIdx.x;
   const int G = hq / hkv;
   float acc = 0.f;
   for (int h = g * G; h < (g + 1) * G; ++h) {
     float v = que[h * d + c];
     if (with_bias) {
-      float b = 0.f;
-      for (int j = 0; j < n_ctx; ++j)
-        if (j != i) b += wgt[j * hq + h] * loc[((size_t)j * hq + h) * d + c];
-      v += b / (float)(n_ctx - 1);
+      const float others = bias[h * d + c] - wgt[i * hq + h] * loc[((size_t)i * hq + h) * d + c];
+      v += others / (float)(n_ctx - 1);
     }
     acc += v;
   }
@@ -186,11 +212,12 @@ __global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, con
 template <bool BF16, int D>
 hipError_t run(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s) {
   const bool bias = a.q_loc != nullptr && a.n_ctx > 1;
-  dim3 gp(a.hq, bias ? a.n_ctx : 1);
-  hipLaunchKernelGGL((k_pool<BF16, D>), gp, dim3(256), 0, s, a.q_tok, a.n_q_tok, bias ? a.q_loc : nullptr, a.w_loc,
-                     a.hq, a.ws_que, a.ws_loc, a.ws_w);
-  hipLaunchKernelGGL(k_qtilde, dim3(a.n_ctx, a.hkv), dim3(D), 0, s, a.ws_que, a.ws_loc, a.ws_w, a.ws_qt, a.n_ctx,
-                     a.hq, a.hkv, D, bias ? 1 : 0);
+  hipLaunchKernelGGL((k_pool<BF16, D>), dim3(a.hq, bias ? a.n_ctx + 1 : 1), dim3(256), 0, s, a.q_tok, a.n_q_tok,
+                     a.q_loc, a.w_loc, a.hq, a.ws_que, a.ws_loc);
+  if (bias)
+    hipLaunchKernelGGL(k_bias, dim3(a.hq), dim3(1024), 0, s, a.ws_que, a.ws_loc, a.ws_w, a.ws_base, a.n_ctx, a.hq, D);
+  hipLaunchKernelGGL(k_qtilde, dim3(a.n_ctx, a.hkv), dim3(D), 0, s, a.ws_que, a.ws_base, a.ws_loc, a.ws_w, a.ws_qt,
+                     a.n_ctx, a.hq, a.hkv, D, bias ? 1 : 0);
   constexpr int TILE = (64 / (D / (BF16 ? 8 : 4))) * 8 * 2 * 4;
   dim3 gs((a.max_len + TILE - 1) / TILE, a.n_ctx, a.hkv);
   hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_qt, a.scores, a.hkv, a.total_len);

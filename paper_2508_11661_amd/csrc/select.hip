@@ -59,13 +59,11 @@ __global__ __launch_bounds__(NT) void k_select(const float* scores, IntTable cu_
   uint32_t prefix = 0;
   uint32_t kk = (uint32_t)k;
   for (int b = 31; b >= 0; --b) {
-    const uint32_t hi_mask = (b == 31) ? 0u : (0xFFFFFFFFu << (b + 1));
+    // candidate: agrees with the decided bits above b and has bit b set (padding keys are 0: never)
+    const uint32_t want = (prefix >> b) | 1u;
     uint32_t c = 0;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const bool cand = (p0 + e < L) && ((key[e] & hi_mask) == prefix) && ((key[e] >> b) & 1u);
-      c += __popcll(__ballot(cand));
-    }
+    for (int e = 0; e < E; ++e) c += __popcll(__ballot((key[e] >> b) == want));
     if (lane == 0) cnt[b & 1][wave] = c;
     __syncthreads();
     uint32_t tot = 0;
@@ -123,8 +121,9 @@ hipError_t run(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu
 }  // namespace
 
 hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s) {
+  // few waves per row keep the 32 barrier rounds short; many rows share a compute unit instead
   if (a.max_len <= 1024) return run<4, 256>(a, cu_len, cu_k, s);
-  if (a.max_len <= 4096) return run<4, 1024>(a, cu_len, cu_k, s);
+  if (a.max_len <= 4096) return run<16, 256>(a, cu_len, cu_k, s);
   if (a.max_len <= 16384) return run<16, 1024>(a, cu_len, cu_k, s);
   return run<64, 1024>(a, cu_len, cu_k, s);
 }
