@@ -87,17 +87,32 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
   const char* kbase = static_cast<const char*>(a.k) + (size_t)kvh * a.m * D * 2;
   const char* vbase = static_cast<const char*>(a.v) + (size_t)kvh * a.m * D * 2;
 
+  // Tile loads: thread t fetches chunk (row t/CPR + i*RSTEP, 16-byte column t%CPR) of K and of V.  The
+  // byte offsets inside a tile are per-thread constants; the tile base is uniform, so a full tile
+  // costs no address arithmetic.  Only the last, ragged tile clamps its rows to the final key.
+  constexpr int CPR = D / 8, RSTEP = 256 / CPR;
+  uint32_t voff[C::CHUNKS];
+#pragma unroll
+  for (int i = 0; i < C::CHUNKS; ++i) voff[i] = (uint32_t)((t / CPR + i * RSTEP) * (D * 2) + (t % CPR) * 16);
   u32x4 rk[C::CHUNKS], rv[C::CHUNKS];
   auto load_tile = [&](int tile) {
     const int k0 = kv_begin + tile * C::BK;
+    const char* kt = kbase + (size_t)k0 * (D * 2);
+    const char* vt = vbase + (size_t)k0 * (D * 2);
+    if (k0 + C::BK <= a.m) {
 #pragma unroll
-    for (int i = 0; i < C::CHUNKS; ++i) {
-      const int c = t + 256 * i;
-      const int row = c / (D / 8), col = c % (D / 8);
-      const int key = min(k0 + row, a.m - 1);
-      const size_t off = (size_t)key * D * 2 + col * 16;
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + off);
-      rv[i] = *reinterpret_cast<const u32x4*>(vbase + off);
+      for (int i = 0; i < C::CHUNKS; ++i) {
+        rk[i] = *reinterpret_cast<const u32x4*>(kt + voff[i]);
+        rv[i] = *reinterpret_cast<const u32x4*>(vt + voff[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < C::CHUNKS; ++i) {
+        const int row = min(t / CPR + i * RSTEP, a.m - 1 - k0);
+        const uint32_t off = (uint32_t)(row * (D * 2) + (t % CPR) * 16);
+        rk[i] = *reinterpret_cast<const u32x4*>(kt + off);
+        rv[i] = *reinterpret_cast<const u32x4*>(vt + off);
+      }
     }
   };
   auto store_tile = [&](int buf) {
@@ -177,15 +192,26 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
       m_run = m_new;
-      float psum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][j], c2, -m_use));
-          s[kb][j] = p;
-          psum += p;
-        }
+        for (int j = 0; j < 16; ++j) s[kb][j] = __builtin_amdgcn_exp2f(fmaf(s[kb][j], c2, -m_use));
+      // weights go to bf16 for the second product; their row sum is taken over the ROUNDED weights
+      // (bf16 pair . (1,1) accumulated in float32), so numerator and denominator see the same weights
+      bf16x8 bp[2][2];
+      float psum = 0.f;
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            bf16x2 pr = {(__bf16)s[kb][8 * s2 + e], (__bf16)s[kb][8 * s2 + e + 1]};
+            bp[kb][s2][e] = pr[0];
+            bp[kb][s2][e + 1] = pr[1];
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+          }
       l_run = fmaf(l_run, alpha, psum);
       if (__any(alpha != 1.f)) {
 #pragma unroll
@@ -198,9 +224,6 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          bf16x8 bp;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) bp[e] = (__bf16)s[kb][8 * s2 + e];
           const int key1 = kb * 32 + 16 * s2 + 4 * h + (i16 >> 2);
 #pragma unroll
           for (int dvb = 0; dvb < NV; ++dvb) {
@@ -210,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
             union { struct { s16x4 lo, hi; } s; bf16x8 v; } av;
             av.s.lo = lo;
             av.s.hi = hi;
-            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp, o[dvb], 0, 0, 0);
+            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
           }
         }
     }
