@@ -4,7 +4,7 @@
 // Both are softmax(scale * q k^T) v with float32 statistics; they differ in the mask and in how the
 // rows are cut into workgroups, so one kernel template serves both.
 //
-// bf16 kernel (k_attn_bf16), one workgroup = 4 waves = 128 query rows, 64 keys per step:
+// bf16 kernel (k_attn_bf16), one workgroup = NW waves (4 or 8) of 32 query rows each, 64 keys per step:
 //   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = the wave's 32 query rows (registers,
 //                 loaded once).  Computing the transpose puts one query row in one lane column, so the
 //                 softmax weights come out of the accumulator already in the B-operand layout of the
@@ -39,21 +39,22 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // ------------------------------------------------------------------------------------------ bf16
-template <int D>
+template <int D, int NW_>
 struct Bf16Cfg {
-  static constexpr int BQ = 128, BK = 64;
+  static constexpr int NW = NW_, NT = 64 * NW;
+  static constexpr int BQ = 32 * NW, BK = 64;
   static constexpr int KSTR = D * 2 + 16;  // bytes per K row in LDS (pad: 16 rows hit 64 distinct banks)
   static constexpr int VSTR = D * 2 + 32;  // bytes per V row in LDS (pad: 4 rows x 32 B of a transposing read are disjoint)
   static constexpr int TILE_BYTES = BK * (KSTR + VSTR);
   static constexpr int LDS_BYTES = 2 * TILE_BYTES;
-  static constexpr int CHUNKS = (BK * D * 2 / 16) / 256;  // 16-byte chunks per thread per tile and tensor
+  static constexpr int CHUNKS = (BK * D * 2 / 16) / NT;  // 16-byte chunks per thread per tile and tensor
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
-  using C = Bf16Cfg<D>;
+template <int D, bool CAUSAL, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
+  using C = Bf16Cfg<D, NW>;
   constexpr int ND = D / 16;   // k-steps of the S^T product
   constexpr int NV = D / 32;   // 32-row blocks of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
   // Tile loads: thread t fetches chunk (row t/CPR + i*RSTEP, 16-byte column t%CPR) of K and of V.  The
   // byte offsets inside a tile are per-thread constants; the tile base is uniform, so a full tile
   // costs no address arithmetic.  Only the last, ragged tile clamps its rows to the final key.
-  constexpr int CPR = D / 8, RSTEP = 256 / CPR;
+  constexpr int CPR = D / 8, RSTEP = C::NT / CPR;
   uint32_t voff[C::CHUNKS];
 #pragma unroll
   for (int i = 0; i < C::CHUNKS; ++i) voff[i] = (uint32_t)((t / CPR + i * RSTEP) * (D * 2) + (t % CPR) * 16);
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bf16(AttnArgs a) {
     char* sv = sk + C::BK * C::KSTR;
 #pragma unroll
     for (int i = 0; i < C::CHUNKS; ++i) {
-      const int c = t + 256 * i;
+      const int c = t + C::NT * i;
       const int row = c / (D / 8), col = c % (D / 8);
       *reinterpret_cast<u32x4*>(sk + row * C::KSTR + col * 16) = rk[i];
       *reinterpret_cast<u32x4*>(sv + row * C::VSTR + col * 16) = rv[i];
@@ -408,20 +409,25 @@ AttnArgs make_args(const AttnLaunch& l) {
   return a;
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, int NW>
 hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
-  using C = Bf16Cfg<D>;
+  using C = Bf16Cfg<D, NW>;
   static bool attr_set = false;  // per process; the attribute belongs to the function, not the stream
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   AttnArgs a = make_args(l);
   dim3 grid(l.n_batch, (l.rows + C::BQ - 1) / C::BQ, a.n_split);
-  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL>), grid, dim3(256), C::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
   return hipGetLastError();
+}
+
+template <int D, bool CAUSAL>
+hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
+  return attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8 ? run_bf16<D, CAUSAL, 8>(l, s) : run_bf16<D, CAUSAL, 4>(l, s);
 }
 
 template <int D, bool CAUSAL>
@@ -435,8 +441,8 @@ hipError_t run_f32(const AttnLaunch& l, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
-  if (l.d == 128) return l.causal ? run_bf16<128, true>(l, s) : run_bf16<128, false>(l, s);
-  return l.causal ? run_bf16<64, true>(l, s) : run_bf16<64, false>(l, s);
+  if (l.d == 128) return l.causal ? run_bf16_nw<128, true>(l, s) : run_bf16_nw<128, false>(l, s);
+  return l.causal ? run_bf16_nw<64, true>(l, s) : run_bf16_nw<64, false>(l, s);
 }
 
 hipError_t launch_attn_f32(const AttnLaunch& l, hipStream_t s) {

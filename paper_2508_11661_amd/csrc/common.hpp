@@ -70,6 +70,14 @@ struct GatherLaunch {
 hipError_t launch_gather(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
                          const IntTable& cu_k, hipStream_t s);
 
+// Waves per workgroup of the bf16 attention kernel (each wave owns 32 query rows).  Eight waves share
+// one K/V tile stream between twice as many rows; that pays once there are enough row tiles to keep
+// every compute unit busy, otherwise four waves give more workgroups to spread.
+inline int attn_bf16_waves(int causal, int n_batch, int rows) {
+  if (causal) return (long long)n_batch * ((rows + 255) / 256) >= 1024 ? 8 : 4;
+  return rows >= 1024 ? 8 : 4;
+}
+
 // One attention problem: `n_batch` independent row blocks, batch b reads KV head b / batch_per_kv.
 // Row r of a batch attends keys [0, r] (causal) or [0, m) (not causal).
 struct AttnLaunch {

@@ -80,7 +80,7 @@ ScoreWs score_ws(int n_ctx, int hq, int hkv, int d) {
 // Not-causal attention: cut the keys into chunks when the row tiles alone cannot fill the chip.
 struct SplitPlan { int n_split, chunk; size_t part_o, part_lse, bytes; };
 SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
-  const int bq = dtype == SAMKV_BF16 ? 128 : 16;
+  const int bq = dtype == SAMKV_BF16 ? 32 * attn_bf16_waves(0, n_batch, rows) : 16;
   const int bk = dtype == SAMKV_BF16 ? 64 : 32;
   const long long base = (long long)((rows + bq - 1) / bq) * n_batch;
   const int key_tiles = (m + bk - 1) / bk;
