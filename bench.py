@@ -44,15 +44,24 @@ def algorithmic_work(w, lens, m, n_q_tok):
     }
 
 
-def read_traffic(kernel_file: str):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (or None)."""
-    path = os.path.join(ROOT, "profiles", kernel_file)
+def read_traffic(workload, kernel: str):
+    """HBM bytes per launch (read + write) of a kernel, from the committed rocprofv3 --pmc summary of this
+    workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
+    prefix = {"score": "k_score", "select": "k_select", "gather": "k_gather",
+              "recompute_attn": "k_attn_%s<%d, true" % (workload.dtype, workload.head_dim),
+              "query_attn": "k_attn_%s<%d, false" % (workload.dtype, workload.head_dim)}[kernel]
     try:
-        text = open(path).read()
+        lines = open(os.path.join(ROOT, "profiles", f"bench_{workload.name}.txt")).read().splitlines()
     except OSError:
         return None
-    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
-    return float(m.group(1)) if m else None
+    for line in lines:
+        if line.startswith(prefix):
+            try:
+                rd, wr = float(line.split()[-2]), float(line.split()[-1])
+                return (rd + wr) * 1e6
+            except ValueError:
+                return None
+    return None
 
 
 def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
@@ -105,6 +114,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="layers of a multi-layer workload to run (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies (known traffic, for scaling rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -173,6 +185,13 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     work = algorithmic_work(w, w.lens, m, w.n_q_tok)
     per_kernel = {}
     for name in KERNELS:
@@ -196,7 +215,8 @@ def main() -> int:
         roof = {"kernel": dom, "bound": "hbm", "achieved": per_kernel[dom]["GB/s"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(per_kernel[dom]["GB/s"] / HBM_PEAK_GBS, 4)}
     roof["avg_launch_ms"] = per_kernel[dom]["ms"]
-    roof["traffic"] = read_traffic(f"{dom}_{w.name}.pmc.txt")
+    roof["traffic"] = read_traffic(w, dom)
+    roof["algorithmic"] = work[dom]["flops"] if roof["bound"] != "hbm" else work[dom]["bytes"]
 
     out = {
         "metric": "KV tokens scored per second through the whole sparse-prefill hot path "

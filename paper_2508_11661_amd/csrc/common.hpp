@@ -29,16 +29,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// document that owns compacted position m: largest i with cu[i] <= m
-__device__ __forceinline__ int find_ctx(const IntTable& cu, int n_ctx, int m) {
-  int lo = 0, hi = n_ctx;  // invariant: cu[lo] <= m < cu[hi]
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (cu.v[mid] <= m) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 // ---- host-side launchers (one per translation unit) -------------------------------------------
 struct ScoreLaunch {
   int n_ctx, hq, hkv, d, dtype, n_q_tok, w_loc, max_len, total_len;
