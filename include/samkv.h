@@ -55,8 +55,9 @@ enum {
   SAMKV_EDEVICE = -4       /* the HIP runtime refused a launch */
 };
 
-/* The N independently stored per-document caches of one layer (problem statement of the paper:
- * "each document's KV Cache is computed and stored independently").  Host struct. */
+/* The N per-document caches of one layer.  In the paper's problem statement (Abstract, Sec. 1) every
+ * retrieved document's KV cache was prefilled and stored on its own, without seeing the others.
+ * Host struct. */
 typedef struct {
   int32_t n_ctx;            /* D in the paper: number of documents                              */
   int32_t n_q_heads;        /* Hq                                                                */

@@ -44,7 +44,7 @@ struct Bf16Cfg {
   static constexpr int NW = NW_, NT = 64 * NW;
   static constexpr int BQ = 32 * NW, BK = 64;
   static constexpr int KSTR = D * 2 + 16;  // bytes per K row in LDS (pad: 16 rows hit 64 distinct banks)
-  static constexpr int VSTR = D * 2 + 32;  // bytes per V row in LDS (pad: 4 rows x 32 B of a transposing read are disjoint)
+  static constexpr int VSTR = D * 2 + 64;  // bytes per V row in LDS: the 4 rows x 32 B of a transposing read fall in disjoint bank ranges
   static constexpr int TILE_BYTES = BK * (KSTR + VSTR);
   static constexpr int LDS_BYTES = 2 * TILE_BYTES;
   static constexpr int CHUNKS = (BK * D * 2 / 16) / NT;  // 16-byte chunks per thread per tile and tensor
@@ -269,6 +269,288 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
   }
 }
 
+// ------------------------------------------------------ bf16, d = 128, asynchronous tile loads (LDS DMA)
+// Eight waves x 32 rows, one workgroup per compute unit; same arithmetic and operand layouts as
+// k_attn_bf16, with two changes to how a step is organised.
+//
+// (1) Software pipeline.  The products of the NEXT tile's scores are issued in the same straight-line
+//     block as the softmax of the CURRENT tile, so the matrix pipe and the vector ALU of a SIMD work at
+//     the same time without relying on a second wave being in the other phase:
+//         step t:   S(t+1) = K(t+1) Q^T      (MFMA)   |   P(t) = exp2(S(t) c - m)      (VALU)
+//                   O^T   += V(t)^T P(t)^T   (MFMA)
+//     To keep that block free of branches a wave splits its tiles into `n_full` unmasked tiles (this
+//     path) and at most one tail tile (the causal diagonal or the ragged end; plain path with masks),
+//     and the running maximum is only raised when a row outgrows it by more than 2^8 ("lazy rescale"):
+//     weights then stay below 256, which float32 sums and bf16 weights hold without loss, and the
+//     rescale of O becomes a rare side branch ahead of the block.
+// (2) Asynchronous tile loads.  K/V tiles travel from global memory straight into LDS
+//     (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into a ring of three K
+//     slots and three V slots, two tiles ahead of their use, so a load has two full steps to land.
+//
+// A wave-wide DMA instruction fills 1 KB of LDS contiguously (lane i -> base + 16 i), i.e. four 256-byte
+// rows with no room for padding, so the tiles are stored unpadded and XOR-swizzled instead: the 16-byte
+// chunk c of row r sits at chunk position c ^ (r & 15) for K (16 consecutive rows of one fragment read
+// land in 16 different bank groups) and at c ^ 2 (r & 7) for V (the 4 rows x 32 B of a transposing read
+// land in disjoint bank ranges).  Which global chunk a lane fetches is free, so the swizzle costs nothing
+// on the load side; on the read side it is folded into per-lane address registers.
+template <bool CAUSAL>
+__global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
+  constexpr int D = 128, NW = 8, BQ = 32 * NW, BK = 64;
+  constexpr int ND = D / 16, NV = D / 32;
+  constexpr int TILE = BK * D * 2;  // 16 KB, unpadded
+  constexpr int NSLOT = 3;
+  constexpr float TAU = 8.f;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // K(j) in slot j % 3 at smem + slot * TILE; V(j) in slot j % 3 at smem + (3 + slot) * TILE
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int rw = lane & 31, h = lane >> 5;
+  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  const int q0 = qt * BQ;
+  const int n_kv = a.n_batch / a.batch_per_kv;
+  const int kvh = blockIdx.x % n_kv;
+  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
+  const int split = blockIdx.z;
+  const int kv_begin = CAUSAL ? 0 : split * a.chunk;
+  const int kv_end = CAUSAL ? min(a.m, q0 + BQ) : min(a.m, kv_begin + a.chunk);
+  const int span = kv_end - kv_begin;
+  const int n_tiles = (span + BK - 1) / BK;
+
+  const int r = q0 + wave * 32 + rw;
+  const int r_c = min(r, a.rows - 1);
+  const int wave_first = q0 + wave * 32;
+  const int n_full = CAUSAL ? min((wave_first + 1) / BK, span / BK) : span / BK;
+  const bool has_tail = n_full * BK < span;
+
+  bf16x8 bq[ND];
+  {
+    const char* qp = static_cast<const char*>(a.q) + ((size_t)batch * a.rows + r_c) * D * 2 + h * 16;
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) bq[dc] = *reinterpret_cast<const bf16x8*>(qp + dc * 32);
+  }
+  const char* kbase = static_cast<const char*>(a.k) + ((size_t)kvh * a.m + kv_begin) * D * 2;
+  const char* vbase = static_cast<const char*>(a.v) + ((size_t)kvh * a.m + kv_begin) * D * 2;
+
+  // ---- DMA side: wave w, instruction i fills rows 4 (2w + i) .. + 3 of a tile; lane L lands at chunk
+  //      position L & 15 of row 4 (2w + i) + (L >> 4) and therefore fetches the chunk that belongs there
+  uint32_t goff_k[2], goff_v[2];
+  int grow[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = 4 * (2 * wave + i) + (lane >> 4), pos = lane & 15;
+    grow[i] = row;
+    goff_k[i] = (uint32_t)(row * (D * 2) + ((pos ^ (row & 15)) * 16));
+    goff_v[i] = (uint32_t)(row * (D * 2) + ((pos ^ (2 * (row & 7))) * 16));
+  }
+  // The DMA is issued through inline assembly on purpose: the compiler then neither orders later LDS
+  // reads behind it (it would drain every outstanding load before each fragment read) nor counts it in
+  // its own vmcnt bookkeeping; arrival is awaited by hand (s_waitcnt vmcnt) ahead of the barriers.
+  auto dma16 = [&](const char* tile_base, uint32_t byte_off, const char* lds_dst) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(const __attribute__((address_space(3))) char*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(m0v), "v"(byte_off), "s"(tile_base)
+                 : "memory", "m0");
+  };
+  auto dma_tile = [&](const char* base, int j, char* slot, const uint32_t (&goff)[2], bool is_v) {
+    const int k0 = j * BK;
+    const char* tp = base + (size_t)k0 * (D * 2);
+    if (kv_begin + k0 + BK <= a.m) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) dma16(tp, goff[i], slot + (2 * wave + i) * 1024);
+    } else {
+      // last tile of the cache: rows past the final key re-read that key (their scores are masked)
+      const int last = a.m - 1 - kv_begin - k0;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int row = grow[i], pos = lane & 15;
+        const int src_chunk = is_v ? (pos ^ (2 * (row & 7))) : (pos ^ (row & 15));
+        const uint32_t off = (uint32_t)(min(row, last) * (D * 2) + src_chunk * 16);
+        dma16(tp, off, slot + (2 * wave + i) * 1024);
+      }
+    }
+  };
+  auto kslot = [&](int j) { return smem + (j % NSLOT) * TILE; };
+  auto vslot = [&](int j) { return smem + (NSLOT + j % NSLOT) * TILE; };
+
+  // ---- read side: per-lane swizzled byte offsets inside a slot
+  uint32_t kaddr[ND], vaddr[NV];
+  {
+    const int x = rw & 15;
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) kaddr[dc] = (uint32_t)(rw * 256 + (((2 * dc + h) ^ x) * 16));
+    const int i16 = lane & 15, q2 = (lane >> 4) & 1;
+    const int vrow = 4 * h + (i16 >> 2);       // + kb*32 + s2*16 (+8): multiples of 8, do not change row & 7
+    const int xv = 2 * (vrow & 7);
+#pragma unroll
+    for (int dvb = 0; dvb < NV; ++dvb) {
+      const int c = 4 * dvb + 2 * q2 + ((i16 & 3) >> 1);
+      vaddr[dvb] = (uint32_t)(vrow * 256 + ((c ^ xv) * 16) + 8 * (i16 & 1));
+    }
+  }
+
+  f32x16 o[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;
+  const float c2 = a.scale * kLog2e;
+
+  auto lift = [&](float mx) {
+    if (__any(mx > m_ref + TAU)) {
+      const float m_new = fmaxf(m_ref, mx);
+      const float al = __builtin_amdgcn_exp2f(m_ref - m_new);
+      l_run *= al;
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[i][j] *= al;
+      m_ref = m_new;
+    }
+  };
+  auto row_max = [&](const f32x16 (&s)[2]) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    return mx * c2;
+  };
+  auto kfrags = [&](const char* ks, int kb, bf16x8 (&ak)[ND]) {
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) ak[dc] = *reinterpret_cast<const bf16x8*>(ks + kaddr[dc] + kb * 32 * 256);
+  };
+  auto weights_pv = [&](f32x16 (&s)[2], const char* vs, float m_use) {
+    bf16x8 bp[2][2];
+    float psum = 0.f;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * s2 + e], c2, -m_use));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * s2 + e + 1], c2, -m_use));
+          bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+          bp[kb][s2][e] = pr[0];
+          bp[kb][s2][e + 1] = pr[1];
+          psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+        }
+    l_run += psum;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int dvb = 0; dvb < NV; ++dvb) {
+          const char* vp = vs + vaddr[dvb] + (kb * 32 + s2 * 16) * 256;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * 256));
+          union { struct { s16x4 lo, hi; } s; bf16x8 v; } av;
+          av.s.lo = lo;
+          av.s.hi = hi;
+          o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
+        }
+  };
+
+  // ---- prologue: K(0), V(0), K(1) must have landed; V(1), K(2) stay in flight
+  dma_tile(kbase, 0, kslot(0), goff_k, false);
+  dma_tile(vbase, 0, vslot(0), goff_v, true);
+  if (n_tiles > 1) dma_tile(kbase, 1, kslot(1), goff_k, false);
+  if (n_tiles > 1) dma_tile(vbase, 1, vslot(1), goff_v, true);
+  if (n_tiles > 2) dma_tile(kbase, 2, kslot(2), goff_k, false);
+  if (n_tiles > 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);        // vmcnt(4): everything but V(1), K(2)
+  else if (n_tiles > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);   // vmcnt(2): everything but V(1)
+  else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  f32x16 sA[2], sB[2];
+  {
+    bf16x8 ak0[ND], ak1[ND];
+    kfrags(kslot(0), 0, ak0);
+    kfrags(kslot(0), 1, ak1);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { sA[0][j] = 0.f; sA[1][j] = 0.f; }
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) sA[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0[dc], bq[dc], sA[0], 0, 0, 0);
+#pragma unroll
+    for (int dc = 0; dc < ND; ++dc) sA[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1[dc], bq[dc], sA[1], 0, 0, 0);
+  }
+  __builtin_amdgcn_s_barrier();  // K(0) has been read by every wave before step 0 refills its slot with K(3)
+
+  // step `tile`: S(tile) is in sc; computes S(tile + 1) into sn and adds tile's V contribution
+  auto step = [&](int tile, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+    const bool more_k = tile + 3 < n_tiles, more_v = tile + 2 < n_tiles;
+    if (more_k) dma_tile(kbase, tile + 3, kslot(tile + 3), goff_k, false);
+    if (more_v) dma_tile(vbase, tile + 2, vslot(tile + 2), goff_v, true);
+    const char* k_next = kslot(tile + 1);
+    const char* v_cur = vslot(tile);
+    if (tile < n_full) {
+      bf16x8 ak0[ND], ak1[ND];
+      kfrags(k_next, 0, ak0);
+      __builtin_amdgcn_sched_barrier(0);
+      lift(row_max(sc));
+      kfrags(k_next, 1, ak1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) { sn[0][j] = 0.f; sn[1][j] = 0.f; }
+#pragma unroll
+      for (int dc = 0; dc < ND; ++dc) sn[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak0[dc], bq[dc], sn[0], 0, 0, 0);
+#pragma unroll
+      for (int dc = 0; dc < ND; ++dc) sn[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak1[dc], bq[dc], sn[1], 0, 0, 0);
+      weights_pv(sc, v_cur, m_ref);
+    } else if (tile == n_full && has_tail) {
+      const int k0 = kv_begin + tile * BK;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int key = k0 + kb * 32 + 8 * (j >> 2) + 4 * h + (j & 3);
+          if (key >= kv_end || (CAUSAL && key > r)) sc[kb][j] = -INFINITY;
+        }
+      lift(row_max(sc));
+      weights_pv(sc, v_cur, m_ref == -INFINITY ? 0.f : m_ref);
+    }
+    // the tiles needed by the next step were requested one step ago: wait for all but this step's loads
+    if (more_k) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);
+    else if (more_v) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+  };
+  for (int tile = 0; tile < n_tiles; tile += 2) {
+    step(tile, sA, sB);
+    if (tile + 1 < n_tiles) step(tile + 1, sB, sA);
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = 1.f / l_tot;
+  if (r < a.rows) {
+    const size_t row_id = (size_t)batch * a.rows + r;
+    float* op;
+    float* lp;
+    if (a.n_split > 1) {
+      const size_t prow = (size_t)split * a.n_batch * a.rows + row_id;
+      op = a.part_o + prow * D;
+      lp = a.part_lse + prow;
+    } else {
+      op = a.out + row_id * D;
+      lp = a.lse + row_id;
+    }
+#pragma unroll
+    for (int dvb = 0; dvb < NV; ++dvb)
+#pragma unroll
+      for (int j4 = 0; j4 < 4; ++j4) {
+        f32x4 x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
+        *reinterpret_cast<f32x4*>(op + dvb * 32 + 8 * j4 + 4 * h) = x;
+      }
+    if (h == 0) *lp = (m_ref + __log2f(l_tot)) * kLn2;
+  }
+}
+
 // ------------------------------------------------------------------------------------------- f32
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
@@ -425,8 +707,28 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <bool CAUSAL>
+hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
+  constexpr int LDS = 6 * 64 * 256;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<CAUSAL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  AttnArgs a = make_args(l);
+  dim3 grid(l.n_batch, (l.rows + 255) / 256, a.n_split);
+  hipLaunchKernelGGL((k_attn_bf16_dma<CAUSAL>), grid, dim3(512), LDS, s, a);
+  return hipGetLastError();
+}
+
 template <int D, bool CAUSAL>
 hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
+  // the asynchronous kernel serves the long causal problems (d = 128, enough row tiles for 8 waves)
+  if constexpr (CAUSAL && D == 128) {
+    if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16_dma<true>(l, s);
+  }
   return attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8 ? run_bf16<D, CAUSAL, 8>(l, s) : run_bf16<D, CAUSAL, 4>(l, s);
 }
 
