@@ -319,7 +319,10 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   const int r = q0 + wave * 32 + rw;
   const int r_c = min(r, a.rows - 1);
   const int wave_first = q0 + wave * 32;
-  const int n_full = CAUSAL ? min((wave_first + 1) / BK, span / BK) : span / BK;
+  // Without a mask every tile but a ragged last one is full: n_full = span / BK.  It is written as a
+  // per-wave quantity on purpose (the first operand of the min is always the larger one): with a
+  // workgroup-uniform bound the compiler re-versions the step loop and spills registers.
+  const int n_full = CAUSAL ? min((wave_first + 1) / BK, span / BK) : min((wave_first + (1 << 24)) / BK, span / BK);
   const bool has_tail = n_full * BK < span;
 
   bf16x8 bq[ND];
@@ -726,8 +729,8 @@ hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
 template <int D, bool CAUSAL>
 hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
   // the asynchronous kernel serves the long causal problems (d = 128, enough row tiles for 8 waves)
-  if constexpr (CAUSAL && D == 128) {
-    if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16_dma<true>(l, s);
+  if constexpr (D == 128) {
+    if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16_dma<CAUSAL>(l, s);
   }
   return attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8 ? run_bf16<D, CAUSAL, 8>(l, s) : run_bf16<D, CAUSAL, 4>(l, s);
 }
