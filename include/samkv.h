@@ -15,6 +15,7 @@
  *                         document boundaries: the attention inside the recomputation (Sec. 3.3)
  *   samkv_query_attn      attention of the user query's tokens over the compacted cache: the final
  *                         incremental prefill of the query (Sec. 3.3, last paragraph)
+ *   samkv_kv_update       overwrite or fuse (Eq. 4) recomputed K/V rows into the compacted cache
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer unless the comment says "host".  Host arrays (len,
@@ -140,6 +141,18 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
                      int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                      int32_t dtype, float scale, float* out, float* lse, void* ws, size_t ws_bytes,
                      void* stream);
+
+/* Sec. 3.3, cache update after recomputation.  k_c, v_c [Hkv][M][d] hold the old compacted cache and are
+ * updated in place from the recomputed rows k_new, v_new (same shape and dtype):
+ *   mode SAMKV_OVERWRITE: row <- new row
+ *   mode SAMKV_FUSION (Eq. 4): theta = cos(new row, old row); row <- theta * new + (1 - theta) * old,
+ *     per compacted position and KV head, separately for K and for V; float32 arithmetic, one rounding
+ *     to `dtype` at the end; theta = 1 when either row has norm below 1e-20.
+ * The new rows come from the model's K/V projections of the recomputed tokens, which are outside this
+ * library; samkv_query_attn then attends over the updated cache. */
+enum { SAMKV_OVERWRITE = 0, SAMKV_FUSION = 1 };
+int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, int32_t m_total,
+                    int32_t n_kv_heads, int32_t head_dim, int32_t dtype, int32_t mode, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,7 @@ the order and notation of the paper:
   kept_count           budget ratio -> number of kept tokens per document and head
   select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
   gather               Sec. 3.2: concatenate the kept K/V of all documents in their original order
+  kv_update            Sec. 3.3, Eq. 4: overwrite or cosine-weighted fusion of recomputed K/V rows
   attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
                        incremental prefill of the user query (no mask): softmax(q k^T * scale) v
 
@@ -159,6 +160,27 @@ def gather(k: Sequence[np.ndarray], v: Sequence[np.ndarray], idx: np.ndarray, cu
                 k_c[g, m, :] = k[i][g, idx[g, m], :]
                 v_c[g, m, :] = v[i][g, idx[g, m], :]
     return k_c, v_c
+
+
+# --------------------------------------------------------------------------- cache update (Eq. 4)
+def kv_update(old: np.ndarray, new: np.ndarray, fusion: bool) -> np.ndarray:
+    """Cache update after recomputation, for K or for V alike.  old, new [Hkv, M, d] -> [Hkv, M, d] float64.
+
+    Overwrite: the recomputed rows replace the old ones.  Fusion (Eq. 4): theta = cos(new, old),
+    result = theta * new + (1 - theta) * old, with the cosine taken per cached token and KV head
+    (the paper leaves its granularity open); theta = 1 when either row has (numerically) zero norm."""
+    old = np.asarray(old, F64)
+    new = np.asarray(new, F64)
+    if not fusion:
+        return new.copy()
+    out = np.empty_like(old)
+    for g in range(old.shape[0]):
+        for m in range(old.shape[1]):
+            a, b = new[g, m], old[g, m]
+            na, nb = math.sqrt(float(a @ a)), math.sqrt(float(b @ b))
+            theta = 1.0 if (na < 1e-20 or nb < 1e-20) else float(a @ b) / (na * nb)
+            out[g, m] = theta * a + (1.0 - theta) * b
+    return out
 
 
 # --------------------------------------------------------------------------- attention

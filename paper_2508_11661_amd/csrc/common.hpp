@@ -87,4 +87,13 @@ hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnLaunch& a, hipStream_t s);
 
+// Cache update after recomputation: rows of `cur` (old, updated in place) against rows of `fresh` (new).
+struct UpdateLaunch {
+  int dtype, d, fusion;
+  long long n_rows;   // per tensor (K and V each have n_rows rows of d elements)
+  void* k_cur; void* v_cur;
+  const void* k_new; const void* v_new;
+};
+hipError_t launch_kv_update(const UpdateLaunch& a, hipStream_t s);
+
 }  // namespace samkv

@@ -247,4 +247,17 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
   return dev(e);
 }
 
+int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, int32_t m_total, int32_t n_kv_heads,
+                    int32_t head_dim, int32_t dtype, int32_t mode, void* stream) {
+  if (k_c == nullptr || v_c == nullptr || k_new == nullptr || v_new == nullptr) return SAMKV_EINVAL;
+  if (m_total < 1 || n_kv_heads < 1 || (mode != SAMKV_OVERWRITE && mode != SAMKV_FUSION)) return SAMKV_EINVAL;
+  if (dtype != SAMKV_F32 && dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
+  if (head_dim != 64 && head_dim != 128) return SAMKV_EUNSUPPORTED;
+  UpdateLaunch a;
+  a.dtype = dtype; a.d = head_dim; a.fusion = mode == SAMKV_FUSION;
+  a.n_rows = (long long)m_total * n_kv_heads;
+  a.k_cur = k_c; a.v_cur = v_c; a.k_new = k_new; a.v_new = v_new;
+  return dev(launch_kv_update(a, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -18,7 +18,8 @@ SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_workspace_bytes", "samkv_score", "samkv_topk_select",
-           "samkv_gather", "samkv_recompute_attn", "samkv_query_attn")
+           "samkv_gather", "samkv_recompute_attn", "samkv_query_attn", "samkv_kv_update")
+SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
 
 class _Caches(ctypes.Structure):
@@ -52,6 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_recompute_attn.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_query_attn.restype = ctypes.c_int
     lib.samkv_query_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.samkv_kv_update.restype = ctypes.c_int
+    lib.samkv_kv_update.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     return lib
 
 
@@ -181,6 +184,15 @@ def samkv_query_attn(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, 
                                  scale, _ptr(out), _ptr(lse), _ptr(ws),
                                  ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
            "samkv_query_attn")
+
+
+def samkv_kv_update(k_c: torch.Tensor, v_c: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, mode: int) -> None:
+    """k_c, v_c [Hkv, M, d] <- overwrite (mode 0) or cosine-weighted fusion (mode 1, Eq. 4) with k_new, v_new."""
+    hkv, m, d = k_c.shape
+    for t in (v_c, k_new, v_new):
+        assert t.shape == k_c.shape and t.dtype == k_c.dtype
+    _check(_lib.samkv_kv_update(_ptr(k_c), _ptr(v_c), _ptr(k_new), _ptr(v_new), m, hkv, d, _dtype_code(k_c.dtype),
+                                mode, _stream()), "samkv_kv_update")
 
 
 # ------------------------------------------------------------------------------------------------

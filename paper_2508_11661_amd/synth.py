@@ -238,6 +238,16 @@ def make_q_rec(w: Workload, layer: int, n_rows: int) -> np.ndarray:
     return round_to_dtype(z, w.dtype)
 
 
+def make_recomputed_rows(w: Workload, layer: int, old: np.ndarray, sigma: np.ndarray, tensor: int) -> np.ndarray:
+    """Stand-in for the K (tensor=0) or V (tensor=1) rows a model would recompute for the kept tokens:
+    the old rows [Hkv, M, d] plus channel-scaled noise of relative size 0.45, which puts the cosine between
+    new and old rows near the 0.9 the paper reports for its fusion weight (Sec. 3.3)."""
+    rng = np.random.default_rng(np.random.SeedSequence([BASE_SEED + w.cfg_id, layer, 100 + tensor]))
+    z = rng.standard_normal(old.shape, dtype=np.float32)
+    new = old.astype(np.float32) + 0.45 * sigma.astype(np.float32)[:, None, :] * z
+    return round_to_dtype(new, w.dtype)
+
+
 def make_small(seed: int, dtype: str, lens: List[int], n_q_heads: int, n_kv_heads: int, head_dim: int,
                n_q_tok: int, w_loc: int, planted: float = 0.1, dup: float = 0.05) -> LayerInputs:
     """Ad-hoc small workload for tests (ragged document lengths, odd sizes)."""

@@ -212,3 +212,28 @@ def test_outputs_are_deterministic(S):
         runs.append([t.clone() for t in (buf.scores, buf.idx, buf.k_c, buf.rec_out, buf.q_out, buf.q_lse)])
     for a, b in zip(*runs):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_kv_update_overwrite_and_fusion(S, dtype, d):
+    """Eq. 4 on the compacted cache.  float32 caches: relative 1e-5 of the row norm.  bf16 caches: the result is
+    rounded to bf16 once, so it may sit one bf16 step (2^-8 relative) from the rounded oracle value."""
+    import torch
+    x = synth.make_small(31, dtype, [300, 77, 129], 4, 2, d, 3, 2)
+    ref = H.oracle_front(x, 0.5)
+    w = x.workload
+    k_new = synth.make_recomputed_rows(w, 0, ref.k_c, x.sigma_k, 0)
+    v_new = synth.make_recomputed_rows(w, 0, ref.v_c, x.sigma_v, 1)
+    k_new[0, 5] = 0.0                      # a zero row: the cosine is undefined, the new row is taken
+    for mode, fusion in ((S.SAMKV_OVERWRITE, False), (S.SAMKV_FUSION, True)):
+        k_c, v_c = H.to_dev(ref.k_c, dtype), H.to_dev(ref.v_c, dtype)
+        S.samkv_kv_update(k_c, v_c, H.to_dev(k_new, dtype), H.to_dev(v_new, dtype), mode)
+        for got, old, new in ((k_c, ref.k_c, k_new), (v_c, ref.v_c, v_new)):
+            want = O.kv_update(old, new, fusion)
+            g = got.float().cpu().numpy().astype(np.float64)
+            if not fusion:
+                assert np.array_equal(g, want)
+                continue
+            row = np.linalg.norm(want, axis=2, keepdims=True)
+            tol = 1e-5 * row + 1e-7 if dtype == "f32" else 2.0 ** -8 * np.abs(want) + 1e-5 * row + 1e-7
+            assert np.all(np.abs(g - want) <= tol), f"max excess {(np.abs(g - want) - tol).max():.3e}"

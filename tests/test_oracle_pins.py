@@ -410,3 +410,39 @@ def test_full_budget_pipeline_is_dense_attention_over_concatenated_caches():
     q_rec = rng(18).standard_normal((4, 29, 8))
     o, _ = O.attention(q_rec, k_c, v_c, scale, True)
     assert np.allclose(o, _sdpa(q_rec, kk, vv, scale, True), atol=1e-12)
+
+
+# ------------------------------------------------------------------ cache update (Eq. 4)
+def test_kv_update_hand_values_and_closed_forms():
+    # old (1,0), new (1,1): theta = 1/sqrt(2); result = theta (1,1) + (1-theta) (1,0) = (1, theta)
+    th = 1.0 / math.sqrt(2.0)
+    out = O.kv_update(np.array([[[1.0, 0.0]]]), np.array([[[1.0, 1.0]]]), True)
+    assert np.allclose(out, [[[1.0, th]]], atol=1e-15)
+    r = rng(20)
+    old = r.standard_normal((2, 5, 8))
+    new = r.standard_normal((2, 5, 8))
+    assert np.array_equal(O.kv_update(old, new, False), new)                      # overwrite
+    assert np.allclose(O.kv_update(old, old, True), old, atol=1e-14)              # new == old: theta = 1, unchanged
+    assert np.allclose(O.kv_update(old, 2.5 * old, True), 2.5 * old, atol=1e-13)  # parallel: theta = 1, new wins
+    assert np.allclose(O.kv_update(old, -old, True), 3.0 * old, atol=1e-13)       # theta = -1: -new + 2 old = 3 old
+    perp = new - (np.einsum("gmc,gmc->gm", new, old) / np.einsum("gmc,gmc->gm", old, old))[..., None] * old
+    assert np.allclose(O.kv_update(old, perp, True), old, atol=1e-12)             # orthogonal: theta = 0, old stays
+    # the cosine is per cached token and head: changing one row leaves every other row's result alone
+    new2 = new.copy()
+    new2[1, 3] *= -4.0
+    a, b = O.kv_update(old, new, True), O.kv_update(old, new2, True)
+    mask = np.ones((2, 5), bool)
+    mask[1, 3] = False
+    assert np.array_equal(a[mask], b[mask]) and not np.allclose(a[1, 3], b[1, 3])
+    # zero rows: theta = 1, the new row is taken
+    z = np.zeros((1, 1, 4))
+    assert np.array_equal(O.kv_update(z, np.ones((1, 1, 4)), True), np.ones((1, 1, 4)))
+    assert np.array_equal(O.kv_update(np.ones((1, 1, 4)), z, True), z)
+
+
+def test_generated_recomputed_rows_have_cosine_near_the_reported_value():
+    x = synth.make_layer(synth.WORKLOADS["llama3_8b_layer"])
+    old = np.concatenate(x.k, axis=1)[:, :500]
+    new = synth.make_recomputed_rows(x.workload, 0, old, x.sigma_k, 0)
+    cos = np.einsum("gmc,gmc->gm", new, old) / (np.linalg.norm(new, axis=2) * np.linalg.norm(old, axis=2))
+    assert 0.85 < np.median(cos) < 0.95     # Sec. 3.3: the fusion weight is "around 0.9"
