@@ -104,6 +104,53 @@ def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
             "sample": sample, "seconds_measured": round(wall, 2), "ms_per_step_extrapolated": round(total * 1e3, 1)}
 
 
+def at_scale(samkv, iters=5):
+    """Kernel timings at the shapes of the largest workload (64 documents x 4096 tokens, 64/8 heads, d = 128,
+    256 query tokens, 15 % budget), where the kernels are bandwidth- or MFMA-bound instead of latency-bound.
+    Shapes only: device-generated Gaussian bf16 tensors, HIP-event timing, the same entry points.  This is
+    context for the roofline fractions; the headline value above stays the timed workload's."""
+    import torch
+    w = __import__("paper_2508_11661_amd.synth", fromlist=["WORKLOADS"]).WORKLOADS["large_cache_stress"]
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=g).to(torch.bfloat16)
+    k = [rnd(w.n_kv_heads, w.ctx_len, w.head_dim) for _ in range(w.n_ctx)]
+    v = [rnd(w.n_kv_heads, w.ctx_len, w.head_dim) for _ in range(w.n_ctx)]
+    caches = samkv.Caches(k, v, w.n_q_heads)
+    q_tok = rnd(w.n_q_heads, w.n_q_tok, w.head_dim)
+    q_loc = rnd(w.n_ctx, w.n_q_heads, w.w_loc, w.head_dim)
+    m = w.n_ctx * samkv.samkv_kept_count(w.ctx_len, 0.15)
+    q_rec = rnd(w.n_q_heads, m, w.head_dim)
+    buf = samkv.alloc_layer_buffers(caches, w.n_q_tok, 0.15)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    calls = {
+        "score": lambda: samkv.samkv_score(caches, q_tok, q_loc, buf.scores, buf.ws),
+        "select": lambda: samkv.samkv_topk_select(buf.scores, caches, 0.15, 0, 0, buf.idx, buf.cu_k_dev, buf.ws),
+        "gather": lambda: samkv.samkv_gather(caches, buf.idx, 0.15, buf.k_c, buf.v_c),
+        "recompute_attn": lambda: samkv.samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws),
+        "query_attn": lambda: samkv.samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws),
+    }
+    work = algorithmic_work(w, w.lens, m, w.n_q_tok)
+    res = {"workload": w.name, "data": "device-generated Gaussian bf16, shapes only", "iters": iters}
+    for name in KERNELS:                      # in path order, so select/gather/attention see real scores and indices
+        calls[name]()
+    torch.cuda.synchronize()
+    for name in KERNELS:
+        ev = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            calls[name]()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
+        res[name] = {"ms": round(ms, 4), "GB/s": round(work[name]["bytes"] / ms / 1e6, 1),
+                     "TFLOP/s": round(work[name]["flops"] / ms / 1e9, 1),
+                     "frac_hbm": round(work[name]["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
+                     "frac_mfma": round(work[name]["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +161,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="layers of a multi-layer workload to run (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
+    ap.add_argument("--no-at-scale", action="store_true",
+                    help="skip the extra kernel timings at the shapes of the large-cache workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (known traffic, for scaling rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -125,7 +174,7 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2508_11661_amd import samkv, synth
-    from tests.helpers import to_dev
+    to_dev = samkv.upload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -235,6 +284,8 @@ def main() -> int:
         "per_kernel": per_kernel,
         "roofline": roof,
     }
+    if not args.no_at_scale and w.name != "large_cache_stress":
+        out["at_scale"] = at_scale(samkv)
     if not args.no_cpu_baseline:
         rows = args.cpu_sample_rows or (m if m <= 2048 else 48)
         out["cpu_baseline"] = cpu_baseline(layers_np[0], ratio, rows)

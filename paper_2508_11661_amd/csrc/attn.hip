@@ -664,24 +664,30 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
   }
 }
 
-// out = sum_s w_s * part_o[s] with w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One thread per
-// channel, one block per 256 / d rows; splits are visited in order, so the result is deterministic.
+// out = sum_s w_s * part_o[s] with w_s = exp(lse_s - lse), lse = log sum_s exp(lse_s).  One thread per four
+// channels (16-byte loads), d/4 threads per row; chunks are visited in order, so the result is deterministic.
 __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a, int d) {
-  const int rpb = 256 / d;
+  const int tpr = d / 4, rpb = 256 / tpr;
   const size_t n_rows = (size_t)a.n_batch * a.rows;
-  const size_t row = (size_t)blockIdx.x * rpb + threadIdx.x / d;
-  const int c = threadIdx.x % d;
+  const size_t row = (size_t)blockIdx.x * rpb + threadIdx.x / tpr;
+  const int c4 = threadIdx.x % tpr;
   if (row >= n_rows) return;
   float mx = -INFINITY;
   for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, a.part_lse[(size_t)s * n_rows + row]);
-  float den = 0.f, acc = 0.f;
+  float den = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < a.n_split; ++s) {
     const float w = expf(a.part_lse[(size_t)s * n_rows + row] - mx);
+    const f32x4 x = *reinterpret_cast<const f32x4*>(a.part_o + ((size_t)s * n_rows + row) * d + c4 * 4);
     den += w;
-    acc = fmaf(w, a.part_o[((size_t)s * n_rows + row) * d + c], acc);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = fmaf(w, x[e], acc[e]);
   }
-  a.out[row * d + c] = acc / den;
-  if (c == 0) a.lse[row] = mx + logf(den);
+  const float inv = 1.f / den;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) acc[e] *= inv;
+  *reinterpret_cast<f32x4*>(a.out + row * d + c4 * 4) = acc;
+  if (c4 == 0) a.lse[row] = mx + logf(den);
 }
 
 AttnArgs make_args(const AttnLaunch& l) {
@@ -757,7 +763,7 @@ hipError_t launch_attn_f32(const AttnLaunch& l, hipStream_t s) {
 
 hipError_t launch_attn_merge(const AttnLaunch& l, hipStream_t s) {
   AttnArgs a = make_args(l);
-  const int rpb = 256 / l.d;
+  const int rpb = 256 / (l.d / 4);
   const size_t n_rows = (size_t)l.n_batch * l.rows;
   hipLaunchKernelGGL(k_attn_merge, dim3((unsigned)((n_rows + rpb - 1) / rpb)), dim3(256), 0, s, a, l.d);
   return hipGetLastError();

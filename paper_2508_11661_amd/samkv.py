@@ -91,6 +91,12 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+def upload(a, dtype: str) -> torch.Tensor:
+    """numpy float32 array whose values are exact in `dtype` ("f32" or "bf16") -> dense device tensor of that dtype."""
+    t = torch.from_numpy(__import__("numpy").ascontiguousarray(a)).cuda()
+    return t.to({"f32": torch.float32, "bf16": torch.bfloat16}[dtype]).contiguous()
+
+
 @dataclass
 class Caches:
     """The per-document K/V caches of one layer: k[i], v[i] are [Hkv, L_i, d] device tensors."""

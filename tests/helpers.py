@@ -23,8 +23,8 @@ def torch_dtype(name: str):
 
 def to_dev(a: np.ndarray, dtype: str):
     """float32 array whose values are exact in `dtype` -> device tensor of that dtype."""
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(torch_dtype(dtype)).contiguous()
+    from paper_2508_11661_amd import samkv
+    return samkv.upload(a, dtype)
 
 
 @dataclass
