@@ -493,10 +493,8 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
     if (tile < n_full) {
       bf16x8 ak0[ND], ak1[ND];
       kfrags(k_next, 0, ak0);
-      __builtin_amdgcn_sched_barrier(0);
       lift(row_max(sc));
       kfrags(k_next, 1, ak1);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < 16; ++j) { sn[0][j] = 0.f; sn[1][j] = 0.f; }
 #pragma unroll

@@ -1,0 +1,83 @@
+"""Attention entry points on shapes chosen to reach every kernel variant and every prologue/tail case:
+one, two, three and four key tiles, ragged last tiles, many heads with few rows (the 8-wave asynchronous
+kernel is picked by row-tile count), key chunks with a merge, both head dims and both dtypes."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import samkv_oracle as O
+from paper_2508_11661_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _data(seed, dtype, hq, hkv, rows, m, d):
+    rng = np.random.default_rng(seed)
+    q = synth.round_to_dtype(rng.standard_normal((hq, rows, d), dtype=np.float32) * 1.5, dtype)
+    k = synth.round_to_dtype(rng.standard_normal((hkv, m, d), dtype=np.float32) * 1.5, dtype)
+    v = synth.round_to_dtype(rng.standard_normal((hkv, m, d), dtype=np.float32) * 2.0, dtype)
+    return q, k, v
+
+
+def _rows(m, n, seed):
+    if m <= n:
+        return None
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 31, 32, 63, 64, 65, 127, 128, 255, 256, 257, m - 2, m - 1]
+    return np.unique(np.clip(np.concatenate([fixed, rng.integers(0, m, size=n)]), 0, m - 1))
+
+
+@pytest.mark.parametrize("dtype,d,hq,hkv,m", [
+    ("bf16", 128, 1024, 8, 1), ("bf16", 128, 1024, 8, 63), ("bf16", 128, 1024, 8, 64), ("bf16", 128, 1024, 8, 65),
+    ("bf16", 128, 1024, 8, 129), ("bf16", 128, 1024, 8, 200), ("bf16", 128, 512, 8, 300), ("bf16", 128, 64, 8, 4200),
+    ("bf16", 128, 128, 16, 2049), ("bf16", 64, 64, 8, 4200), ("bf16", 64, 8, 2, 700), ("bf16", 128, 8, 8, 700),
+    ("f32", 128, 4, 2, 150), ("f32", 64, 8, 1, 97),
+])
+def test_recompute_attention_shapes(dtype, d, hq, hkv, m):
+    import torch
+    from paper_2508_11661_amd import samkv as S
+    q, k, v = _data(m + hq, dtype, hq, hkv, m, m, d)
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((hq, m, d), float("nan"), device="cuda")
+    lse = torch.full((hq, m), float("nan"), device="cuda")
+    S.samkv_recompute_attn(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), scale, out, lse, None)
+    rows = _rows(m, 12 if hq * m > 20000 else m, seed=m)
+    heads = list(range(hq)) if hq <= 64 else sorted({0, 1, hq // 2, hq - 1} | set(range(0, hq, max(1, hq // 24))))
+    G = hq // hkv
+    kv = sorted({h // G for h in heads})
+    remap = {g: n for n, g in enumerate(kv)}
+    o_ref = np.empty((len(heads), m if rows is None else len(rows), d))
+    l_ref = np.empty((len(heads), m if rows is None else len(rows)))
+    for n, h in enumerate(heads):          # one query head at a time against its own KV head
+        o, l = O.attention(q[h:h + 1], k[h // G:h // G + 1], v[h // G:h // G + 1], scale, True, rows=rows)
+        o_ref[n], l_ref[n] = o[0], l[0]
+    sel = slice(None) if rows is None else torch.from_numpy(rows).cuda()
+    got_o = out[heads][:, sel].cpu().numpy()
+    got_l = lse[heads][:, sel].cpu().numpy()
+    H.check_attention(got_o, got_l, o_ref, l_ref, dtype, f"recompute {dtype} d={d} hq={hq} m={m}")
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+
+
+@pytest.mark.parametrize("dtype,d,hq,hkv,lq,m", [
+    ("bf16", 128, 32, 2, 64, 1), ("bf16", 128, 32, 2, 64, 64), ("bf16", 128, 32, 2, 64, 65), ("bf16", 128, 32, 2, 64, 130),
+    ("bf16", 128, 32, 2, 64, 1000), ("bf16", 128, 32, 2, 64, 3001), ("bf16", 128, 64, 8, 256, 5000),
+    ("bf16", 128, 8, 8, 3, 777), ("bf16", 64, 16, 2, 130, 999), ("f32", 128, 4, 2, 5, 333), ("f32", 64, 8, 8, 40, 2100),
+])
+def test_query_attention_shapes(dtype, d, hq, hkv, lq, m):
+    import torch
+    from paper_2508_11661_amd import samkv as S
+    q, k, v = _data(m + lq, dtype, hq, hkv, lq, m, d)
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((hq, lq, d), float("nan"), device="cuda")
+    lse = torch.full((hq, lq), float("nan"), device="cuda")
+    ws = torch.empty((S.samkv_workspace_bytes(1, hq, hkv, d, lq, m),), dtype=torch.uint8, device="cuda")
+    S.samkv_query_attn(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), scale, out, lse, ws)
+    rows = _rows(lq, 24 if hq * lq * m > 3e7 else lq, seed=m)
+    rows = None if rows is None else rows[rows < lq]
+    o_ref, l_ref = O.attention(q, k, v, scale, False, rows=rows)
+    sel = slice(None) if rows is None else torch.from_numpy(rows).cuda()
+    H.check_attention(out[:, sel].cpu().numpy(), lse[:, sel].cpu().numpy(), o_ref, l_ref, dtype,
+                      f"query {dtype} d={d} hq={hq} lq={lq} m={m}")
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
