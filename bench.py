@@ -33,8 +33,11 @@ def algorithmic_work(w, lens, m, n_q_tok):
     """Algorithmic bytes / flops of one pass over one layer (what the method itself must move or compute)."""
     e = 2 if w.dtype == "bf16" else 4
     tot, hkv, hq, d = sum(lens), w.n_kv_heads, w.n_q_heads, w.head_dim
+    # score: every key row read once and one float32 written per token-head, plus the Q rows that Eq. 1 pools
+    # (the user query's and every document's local Q cache), each read once
+    q_rows = hq * n_q_tok + len(lens) * hq * w.w_loc
     return {
-        "score": {"bytes": tot * hkv * (d * e + 4), "flops": 2 * d * tot * hkv},
+        "score": {"bytes": tot * hkv * (d * e + 4) + q_rows * d * e, "flops": 2 * d * tot * hkv},
         "select": {"bytes": tot * hkv * 4 + m * hkv * 4, "flops": 0},
         "gather": {"bytes": m * hkv * (4 * d * e + 4), "flops": 0},
         "recompute_attn": {"bytes": (2 * hq + 2 * hkv) * m * d * e + hq * m * (d + 1) * 4,

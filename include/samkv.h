@@ -120,6 +120,14 @@ int samkv_topk_select(const float* scores, const samkv_caches* caches, float rat
 int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, void* k_c, void* v_c,
                  void* stream);
 
+/* Same compaction for the per-document Q caches the method also stores (Table 2: the notation covers Q
+ * caches as well): q_rec[h][cu_k[i] + m][:] = Q_i[h][idx[h / G][cu_k[i] + m]][:], bit-exact copies.  This
+ * yields the query states of the kept tokens that samkv_recompute_attn takes.
+ *   q_cache  host [n_ctx] of device pointers, document i: [Hq][len[i]][d], dtype of caches
+ *   q_rec    [Hq][M][d] written.   caches->k and caches->v are not read. */
+int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx, float ratio,
+                   void* q_rec, void* stream);
+
 /* Sec. 3.3 recomputation, attention part.  Row p of query head h is the query state of the token
  * that KV head g(h) keeps at compacted position p; it attends to compacted positions 0..p (itself
  * included), across document boundaries:

@@ -14,7 +14,7 @@ the order and notation of the paper:
   score                Sec. 3.2 / Table 2: inner product <Q^_doc-i, K>
   kept_count           budget ratio -> number of kept tokens per document and head
   select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
-  gather               Sec. 3.2: concatenate the kept K/V of all documents in their original order
+  gather, gather_q     Sec. 3.2: concatenate the kept K/V (and stored Q) of all documents in their original order
   kv_update            Sec. 3.3, Eq. 4: overwrite or cosine-weighted fusion of recomputed K/V rows
   attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
                        incremental prefill of the user query (no mask): softmax(q k^T * scale) v
@@ -160,6 +160,20 @@ def gather(k: Sequence[np.ndarray], v: Sequence[np.ndarray], idx: np.ndarray, cu
                 k_c[g, m, :] = k[i][g, idx[g, m], :]
                 v_c[g, m, :] = v[i][g, idx[g, m], :]
     return k_c, v_c
+
+
+def gather_q(q: Sequence[np.ndarray], idx: np.ndarray, cu_k: np.ndarray) -> np.ndarray:
+    """Same compaction for the stored per-document Q caches: q[i] [Hq, L_i, d] -> [Hq, M, d], query head h
+    taking the kept positions of its KV head h // (Hq / Hkv)."""
+    hq, _, d = q[0].shape
+    hkv, M = idx.shape
+    G = hq // hkv
+    out = np.empty((hq, M, d), q[0].dtype)
+    for i in range(len(q)):
+        for h in range(hq):
+            for m in range(int(cu_k[i]), int(cu_k[i + 1])):
+                out[h, m, :] = q[i][h, idx[h // G, m], :]
+    return out
 
 
 # --------------------------------------------------------------------------- cache update (Eq. 4)

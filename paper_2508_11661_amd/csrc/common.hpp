@@ -59,6 +59,9 @@ struct GatherLaunch {
 };
 hipError_t launch_gather(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
                          const IntTable& cu_k, hipStream_t s);
+// Q-cache variant: a.k_c receives [Hq][M][d]; q holds per-document [Hq][L_i][d]
+hipError_t launch_gather_q(const GatherLaunch& a, const PtrTable& q, const IntTable& cu_len, const IntTable& cu_k,
+                           int hq, hipStream_t s);
 
 // Waves per workgroup of the bf16 attention kernel (each wave owns 32 query rows).  Eight waves share
 // one K/V tile stream between twice as many rows; that pays once there are enough row tiles to keep

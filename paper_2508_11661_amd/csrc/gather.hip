@@ -53,6 +53,54 @@ __global__ __launch_bounds__(256) void k_gather(PtrTable kt, PtrTable vt, IntTab
   }
 }
 
+// Q-cache variant: one tensor, one row set per QUERY head h, indexed by the kept positions of its KV head
+// h / group (the stored per-document Q cache supplies the query states of the kept tokens).
+template <int ROW_BYTES>
+__global__ __launch_bounds__(256) void k_gather_q(PtrTable qt, IntTable cu_len, IntTable cu_k, int m_total, int group,
+                                                  const int32_t* idx, char* q_rec) {
+  constexpr int LPR = ROW_BYTES / 16;
+  constexpr int RPS = 64 / LPR;
+  constexpr int STEPS = 8;
+  constexpr int ROWS_PER_BLOCK = RPS * STEPS * 4;
+  const int i = blockIdx.y, h = blockIdx.z, g = h / group;
+  const int k_i = cu_k.v[i + 1] - cu_k.v[i];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int r0 = blockIdx.x * ROWS_PER_BLOCK + wave * (RPS * STEPS);
+  if (r0 >= k_i) return;
+  const int L = cu_len.v[i + 1] - cu_len.v[i];
+  const char* src = static_cast<const char*>(qt.p[i]) + (size_t)h * L * ROW_BYTES + sub * 16;
+  const size_t out0 = ((size_t)h * m_total + cu_k.v[i]) * ROW_BYTES + sub * 16;
+  const int32_t* ip = idx + (size_t)g * m_total + cu_k.v[i];
+  int p[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int r = r0 + s * RPS + rg;
+    p[s] = ip[r < k_i ? r : k_i - 1];
+  }
+  u32x4 x[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int q = p[s] < 0 ? 0 : (p[s] >= L ? L - 1 : p[s]);
+    x[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)q * ROW_BYTES));
+  }
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int r = r0 + s * RPS + rg;
+    if (r < k_i) __builtin_nontemporal_store(x[s], reinterpret_cast<u32x4*>(q_rec + out0 + (size_t)r * ROW_BYTES));
+  }
+}
+
+template <int ROW_BYTES>
+hipError_t run_q(const GatherLaunch& a, const PtrTable& q, const IntTable& cu_len, const IntTable& cu_k, int hq,
+                 hipStream_t s) {
+  constexpr int ROWS_PER_BLOCK = (64 / (ROW_BYTES / 16)) * 8 * 4;
+  dim3 grid((a.max_k + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, a.n_ctx, hq);
+  hipLaunchKernelGGL((k_gather_q<ROW_BYTES>), grid, dim3(256), 0, s, q, cu_len, cu_k, a.m_total, hq / a.hkv, a.idx,
+                     static_cast<char*>(a.k_c));
+  return hipGetLastError();
+}
+
 template <int ROW_BYTES>
 hipError_t run(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
                const IntTable& cu_k, hipStream_t s) {
@@ -71,6 +119,16 @@ hipError_t launch_gather(const GatherLaunch& a, const PtrTable& k, const PtrTabl
     case 128: return run<128>(a, k, v, cu_len, cu_k, s);
     case 256: return run<256>(a, k, v, cu_len, cu_k, s);
     case 512: return run<512>(a, k, v, cu_len, cu_k, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_gather_q(const GatherLaunch& a, const PtrTable& q, const IntTable& cu_len, const IntTable& cu_k,
+                           int hq, hipStream_t s) {
+  switch (a.row_bytes) {
+    case 128: return run_q<128>(a, q, cu_len, cu_k, hq, s);
+    case 256: return run_q<256>(a, q, cu_len, cu_k, hq, s);
+    case 512: return run_q<512>(a, q, cu_len, cu_k, hq, s);
   }
   return hipErrorInvalidValue;
 }

@@ -206,6 +206,29 @@ int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, vo
   return dev(launch_gather(a, kt, vt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
 }
 
+int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx, float ratio, void* q_rec,
+                   void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table(caches, ratio, 0, 0, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  PtrTable qt;
+  memset(&qt, 0, sizeof(qt));
+  for (int i = 0; i < s.n_ctx; ++i) {
+    if (q_cache[i] == nullptr) return SAMKV_EINVAL;
+    qt.p[i] = q_cache[i];
+  }
+  GatherLaunch a;
+  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.row_bytes = s.d * (s.dtype == SAMKV_BF16 ? 2 : 4);
+  a.m_total = cu_k.v[s.n_ctx]; a.idx = idx; a.k_c = q_rec; a.v_c = nullptr;
+  a.max_k = 0;
+  for (int i = 0; i < s.n_ctx; ++i) a.max_k = cu_k.v[i + 1] - cu_k.v[i] > a.max_k ? cu_k.v[i + 1] - cu_k.v[i] : a.max_k;
+  return dev(launch_gather_q(a, qt, s.cu_len, cu_k, s.hq, static_cast<hipStream_t>(stream)));
+}
+
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
                          void* ws, size_t ws_bytes, void* stream) {

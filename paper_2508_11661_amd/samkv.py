@@ -18,7 +18,7 @@ SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_workspace_bytes", "samkv_score", "samkv_topk_select",
-           "samkv_gather", "samkv_recompute_attn", "samkv_query_attn", "samkv_kv_update")
+           "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
 
@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_topk_select.argtypes = [vp, cp, f32, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_gather.restype = ctypes.c_int
     lib.samkv_gather.argtypes = [cp, vp, f32, vp, vp, vp]
+    lib.samkv_gather_q.restype = ctypes.c_int
+    lib.samkv_gather_q.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, f32, vp, vp]
     lib.samkv_recompute_attn.restype = ctypes.c_int
     lib.samkv_recompute_attn.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_query_attn.restype = ctypes.c_int
@@ -164,6 +166,17 @@ def samkv_gather(caches: Caches, idx: torch.Tensor, ratio: float, k_c: torch.Ten
     assert idx.dtype == torch.int32 and k_c.dtype == caches.k[0].dtype and v_c.dtype == caches.k[0].dtype
     _check(_lib.samkv_gather(ctypes.byref(caches.c), _ptr(idx), ratio, _ptr(k_c), _ptr(v_c), _stream()),
            "samkv_gather")
+
+
+def samkv_gather_q(caches: Caches, q_cache: Sequence[torch.Tensor], idx: torch.Tensor, ratio: float,
+                   q_rec: torch.Tensor) -> None:
+    """q_rec [Hq, M, d] <- rows of the per-document Q caches ([Hq, L_i, d]) at the kept positions of each head's KV head."""
+    assert len(q_cache) == caches.n_ctx and idx.dtype == torch.int32
+    for t, L in zip(q_cache, caches.lens):
+        assert t.is_cuda and t.is_contiguous() and tuple(t.shape) == (caches.n_q_heads, L, caches.head_dim)
+        assert t.dtype == caches.k[0].dtype
+    ptrs = (ctypes.c_void_p * caches.n_ctx)(*[t.data_ptr() for t in q_cache])
+    _check(_lib.samkv_gather_q(ctypes.byref(caches.c), ptrs, _ptr(idx), ratio, _ptr(q_rec), _stream()), "samkv_gather_q")
 
 
 def samkv_recompute_attn(q_rec: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, scale: float,

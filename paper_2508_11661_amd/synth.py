@@ -238,6 +238,18 @@ def make_q_rec(w: Workload, layer: int, n_rows: int) -> np.ndarray:
     return round_to_dtype(z, w.dtype)
 
 
+def make_q_cache(w: Workload, layer: int, lens: List[int]) -> List[np.ndarray]:
+    """Stored per-document Q caches, [Hq, L_i, d] each, with K's channel scales."""
+    sk, _ = _channel_scales(w, layer)
+    scale = np.repeat(sk, w.group, axis=0).astype(np.float32)[:, None, :]
+    out = []
+    for i, L in enumerate(lens):
+        z = np.random.default_rng(np.random.SeedSequence([BASE_SEED + w.cfg_id, layer, 200, i])).standard_normal(
+            (w.n_q_heads, L, w.head_dim), dtype=np.float32)
+        out.append(round_to_dtype(z * scale, w.dtype))
+    return out
+
+
 def make_recomputed_rows(w: Workload, layer: int, old: np.ndarray, sigma: np.ndarray, tensor: int) -> np.ndarray:
     """Stand-in for the K (tensor=0) or V (tensor=1) rows a model would recompute for the kept tokens:
     the old rows [Hkv, M, d] plus channel-scaled noise of relative size 0.45, which puts the cosine between

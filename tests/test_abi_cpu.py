@@ -87,6 +87,11 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_gather(ctypes.byref(_caches(S, v=False)), fake, 0.5, fake, fake, None) == -1
     assert L.samkv_gather(ctypes.byref(ok), None, 0.5, fake, fake, None) == -1
     assert L.samkv_gather(ctypes.byref(ok), fake, 2.0, fake, fake, None) == -1
+    qp = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    assert L.samkv_gather_q(ctypes.byref(ok), None, fake, 0.5, fake, None) == -1
+    assert L.samkv_gather_q(ctypes.byref(ok), qp, None, 0.5, fake, None) == -1
+    assert L.samkv_gather_q(ctypes.byref(ok), qp, fake, 0.0, fake, None) == -1
+    assert L.samkv_gather_q(ctypes.byref(ok), (ctypes.c_void_p * 2)(0x1000, None), fake, 0.5, fake, None) == -1
     # attention
     assert L.samkv_recompute_attn(None, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
     assert L.samkv_recompute_attn(fake, fake, fake, 0, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1

@@ -237,3 +237,17 @@ def test_kv_update_overwrite_and_fusion(S, dtype, d):
             row = np.linalg.norm(want, axis=2, keepdims=True)
             tol = 1e-5 * row + 1e-7 if dtype == "f32" else 2.0 ** -8 * np.abs(want) + 1e-5 * row + 1e-7
             assert np.all(np.abs(g - want) <= tol), f"max excess {(np.abs(g - want) - tol).max():.3e}"
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_gather_q_cache_bit_exact(S, dtype, d):
+    import torch
+    x = synth.make_small(41, dtype, [300, 77, 1025, 5], 8, 2, d, 3, 2)
+    ref = H.oracle_front(x, 0.3)
+    q_np = synth.make_q_cache(x.workload, 0, x.lens)
+    caches = H.upload_caches(x)
+    q_dev = [H.to_dev(a, dtype) for a in q_np]
+    m = int(ref.cu_k[-1])
+    q_rec = torch.zeros((8, m, d), dtype=H.torch_dtype(dtype), device="cuda")
+    S.samkv_gather_q(caches, q_dev, torch.from_numpy(ref.idx).cuda(), 0.3, q_rec)
+    assert np.array_equal(q_rec.float().cpu().numpy(), O.gather_q(q_np, ref.idx, ref.cu_k))

@@ -284,6 +284,19 @@ def test_gather_equals_fancy_indexing_and_full_budget_is_concatenation():
     assert v_c.tobytes() == np.concatenate(v, axis=1).tobytes()
 
 
+def test_gather_q_uses_the_kv_heads_positions():
+    r = rng(19)
+    lens = [7, 5]
+    q = [r.standard_normal((4, L, 3)).astype(np.float32) for L in lens]       # 4 query heads, 2 KV heads
+    idx, cu = O.select([r.standard_normal((2, L)) for L in lens], 0.5)
+    out = O.gather_q(q, idx, cu)
+    assert out.shape == (4, int(cu[-1]), 3)
+    for i in range(2):
+        sl = slice(cu[i], cu[i + 1])
+        for h in range(4):
+            assert out[h, sl].tobytes() == q[i][h][idx[h // 2, sl]].tobytes()
+
+
 # ------------------------------------------------------------------ attention
 def _sdpa(q, k, v, scale, causal):
     import torch
