@@ -150,6 +150,17 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
                      int32_t dtype, float scale, float* out, float* lse, void* ws, size_t ws_bytes,
                      void* stream);
 
+/* The same prefill with the query's own keys and values: query token t attends to the whole compacted
+ * cache and to query tokens 0..t (itself included), which is what an incremental prefill of the query
+ * after the cached documents computes (Sec. 3.3, last paragraph).
+ *   k_self, v_self  [Hkv][n_q_tok][d]  the query tokens' own K/V, dtype as the other tensors
+ * Computed as two partial attentions (cache: no mask; self: causal) merged by their log-sum-exp.
+ * Needs a workspace (samkv_workspace_bytes covers it). */
+int samkv_query_attn_self(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
+                          int32_t m_total, const void* k_self, const void* v_self, int32_t n_q_heads,
+                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out,
+                          float* lse, void* ws, size_t ws_bytes, void* stream);
+
 /* Sec. 3.3, cache update after recomputation.  k_c, v_c [Hkv][M][d] hold the old compacted cache and are
  * updated in place from the recomputed rows k_new, v_new (same shape and dtype):
  *   mode SAMKV_OVERWRITE: row <- new row

@@ -18,6 +18,7 @@ the order and notation of the paper:
   kv_update            Sec. 3.3, Eq. 4: overwrite or cosine-weighted fusion of recomputed K/V rows
   attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
                        incremental prefill of the user query (no mask): softmax(q k^T * scale) v
+  attention_with_self  the same prefill with the query tokens' own K/V appended causally
 
 Readings taken where the paper is silent (listed once more in the design notes):
 the local Q cache becomes a vector by the same mean pooling as Q_que; under
@@ -228,4 +229,30 @@ def attention(q: np.ndarray, k_c: np.ndarray, v_c: np.ndarray, scale: float, cau
             z = e.sum()
             out[h, n] = (e / z) @ v_c[g, :last]
             lse[h, n] = m + math.log(z)
+    return out, lse
+
+
+def attention_with_self(q: np.ndarray, k_c: np.ndarray, v_c: np.ndarray, k_self: np.ndarray, v_self: np.ndarray,
+                        scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Incremental prefill of the user query after the compacted cache (Sec. 3.3, last paragraph): query
+    token t attends to every cached token and to query tokens 0..t, itself included.
+
+    q [Hq, Lq, d]; k_c, v_c [Hkv, M, d]; k_self, v_self [Hkv, Lq, d].  Returns O [Hq, Lq, d], LSE [Hq, Lq]."""
+    q = np.asarray(q, F64)
+    hq, lq, d = q.shape
+    hkv = k_c.shape[0]
+    G = hq // hkv
+    out = np.empty((hq, lq, d), F64)
+    lse = np.empty((hq, lq), F64)
+    for h in range(hq):
+        g = h // G
+        for t in range(lq):
+            keys = np.concatenate([np.asarray(k_c[g], F64), np.asarray(k_self[g, : t + 1], F64)], axis=0)
+            vals = np.concatenate([np.asarray(v_c[g], F64), np.asarray(v_self[g, : t + 1], F64)], axis=0)
+            s = (keys @ q[h, t]) * scale
+            m = s.max()
+            e = np.exp(s - m)
+            z = e.sum()
+            out[h, t] = (e / z) @ vals
+            lse[h, t] = m + math.log(z)
     return out, lse

@@ -104,6 +104,19 @@ SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
   return p;
 }
 
+// Workspace of samkv_query_attn_self: two result slots [2][Hq*Lq][d] + [2][Hq*Lq] (cache part, self part),
+// followed by whatever the cache part itself needs for its key chunks.
+struct SelfWs { size_t part_o, part_lse, inner, bytes; };
+SelfWs self_ws(int hq, int hkv, int d, int n_q_tok, int m_total, int dtype) {
+  SelfWs w;
+  const size_t n_rows = (size_t)hq * n_q_tok;
+  w.part_o = 0;
+  w.part_lse = align_up(2 * n_rows * d * 4);
+  w.inner = align_up(w.part_lse + 2 * n_rows * 4);
+  w.bytes = w.inner + plan_splits(dtype, hkv, (hq / hkv) * n_q_tok, m_total, d).bytes;
+  return w;
+}
+
 int check_attn(const void* q, const void* k, const void* v, int rows, int m, int hq, int hkv, int d, int dtype,
                float scale, const float* out, const float* lse) {
   if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || lse == nullptr) return SAMKV_EINVAL;
@@ -141,6 +154,10 @@ size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_head
   size_t b = plan_splits(SAMKV_BF16, n_kv_heads, rows, m_total, head_dim).bytes;
   const size_t c = plan_splits(SAMKV_F32, n_kv_heads, rows, m_total, head_dim).bytes;
   if (c > b) b = c;
+  const size_t e = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, SAMKV_BF16).bytes;
+  const size_t f = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, SAMKV_F32).bytes;
+  if (e > b) b = e;
+  if (f > b) b = f;
   return (a > b ? a : b) + kAlign;
 }
 
@@ -268,6 +285,33 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
   hipError_t e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
   if (e == hipSuccess && p.n_split > 1) e = launch_attn_merge(a, s);
   return dev(e);
+}
+
+int samkv_query_attn_self(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c, int32_t m_total,
+                          const void* k_self, const void* v_self, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t head_dim, int32_t dtype, float scale, float* out, float* lse, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int rc = check_attn(q_tok, k_c, v_c, n_q_tok, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
+  if (rc != SAMKV_OK) return rc;
+  if (k_self == nullptr || v_self == nullptr) return SAMKV_EINVAL;
+  const SelfWs w = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, dtype);
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
+  char* base = static_cast<char*>(ws);
+  const size_t n_rows = (size_t)n_q_heads * n_q_tok;
+  float* part_o = reinterpret_cast<float*>(base + w.part_o);
+  float* part_lse = reinterpret_cast<float*>(base + w.part_lse);
+  // slot 0: the query over the compacted cache (no mask); slot 1: the query over its own K/V (causal)
+  rc = samkv_query_attn(q_tok, n_q_tok, k_c, v_c, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, part_o,
+                        part_lse, base + w.inner, ws_bytes - w.inner, stream);
+  if (rc != SAMKV_OK) return rc;
+  rc = samkv_recompute_attn(q_tok, k_self, v_self, n_q_tok, n_q_heads, n_kv_heads, head_dim, dtype, scale,
+                            part_o + n_rows * head_dim, part_lse + n_rows, nullptr, 0, stream);
+  if (rc != SAMKV_OK) return rc;
+  AttnLaunch a;
+  memset(&a, 0, sizeof(a));
+  a.d = head_dim; a.n_batch = n_q_heads; a.batch_per_kv = n_q_heads / n_kv_heads; a.rows = n_q_tok;
+  a.out = out; a.lse = lse; a.n_split = 2; a.part_o = part_o; a.part_lse = part_lse;
+  return dev(launch_attn_merge(a, static_cast<hipStream_t>(stream)));
 }
 
 int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, int32_t m_total, int32_t n_kv_heads,

@@ -18,7 +18,8 @@ SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_workspace_bytes", "samkv_score", "samkv_topk_select",
-           "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_kv_update")
+           "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
+           "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
 
@@ -55,6 +56,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_recompute_attn.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_query_attn.restype = ctypes.c_int
     lib.samkv_query_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.samkv_query_attn_self.restype = ctypes.c_int
+    lib.samkv_query_attn_self.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_kv_update.restype = ctypes.c_int
     lib.samkv_kv_update.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     return lib
@@ -203,6 +206,19 @@ def samkv_query_attn(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, 
                                  scale, _ptr(out), _ptr(lse), _ptr(ws),
                                  ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
            "samkv_query_attn")
+
+
+def samkv_query_attn_self(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, k_self: torch.Tensor,
+                          v_self: torch.Tensor, scale: float, out: torch.Tensor, lse: torch.Tensor,
+                          ws: torch.Tensor) -> None:
+    """As samkv_query_attn, with the query tokens' own K/V [Hkv, Lq, d] appended causally."""
+    hq, lq, d = q_tok.shape
+    hkv, m, _ = k_c.shape
+    assert tuple(k_self.shape) == (hkv, lq, d) and v_self.shape == k_self.shape and v_c.shape == k_c.shape
+    assert tuple(out.shape) == (hq, lq, d) and tuple(lse.shape) == (hq, lq) and out.dtype == lse.dtype == torch.float32
+    _check(_lib.samkv_query_attn_self(_ptr(q_tok), lq, _ptr(k_c), _ptr(v_c), m, _ptr(k_self), _ptr(v_self), hq, hkv, d,
+                                      _dtype_code(q_tok.dtype), scale, _ptr(out), _ptr(lse), _ptr(ws),
+                                      ws.numel() * ws.element_size(), _stream()), "samkv_query_attn_self")
 
 
 def samkv_kv_update(k_c: torch.Tensor, v_c: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, mode: int) -> None:

@@ -101,6 +101,9 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.0, fake, fake, None, 0, None) == -1
     assert L.samkv_query_attn(fake, 4, fake, fake, 4096, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
     assert L.samkv_query_attn(fake, 0, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, None, fake, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 30, None) == -1
+    assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, fake, fake, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
+    assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, fake, fake, 4, 2, 128, 1, 0.1, fake, fake, fake, 64, None) == -3
     # samkv_kv_update
     assert L.samkv_kv_update(None, fake, fake, fake, 8, 2, 128, 1, 1, None) == -1
     assert L.samkv_kv_update(fake, fake, fake, fake, 0, 2, 128, 1, 1, None) == -1

@@ -81,3 +81,30 @@ def test_query_attention_shapes(dtype, d, hq, hkv, lq, m):
     H.check_attention(out[:, sel].cpu().numpy(), lse[:, sel].cpu().numpy(), o_ref, l_ref, dtype,
                       f"query {dtype} d={d} hq={hq} lq={lq} m={m}")
     assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+
+
+@pytest.mark.parametrize("dtype,d,hq,hkv,lq,m", [
+    ("bf16", 128, 32, 8, 32, 1540), ("bf16", 128, 8, 2, 1, 100), ("bf16", 64, 8, 8, 70, 333), ("bf16", 128, 64, 8, 256, 3000),
+    ("f32", 64, 8, 2, 16, 156), ("f32", 128, 4, 4, 33, 65),
+])
+def test_query_attention_with_self_tail(dtype, d, hq, hkv, lq, m):
+    import torch
+    from paper_2508_11661_amd import samkv as S
+    q, k, v = _data(7 * m + lq, dtype, hq, hkv, lq, m, d)
+    _, ks, vs = _data(11 * m + lq, dtype, hq, hkv, lq, lq, d)
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((hq, lq, d), float("nan"), device="cuda")
+    lse = torch.full((hq, lq), float("nan"), device="cuda")
+    ws = torch.empty((S.samkv_workspace_bytes(1, hq, hkv, d, lq, m),), dtype=torch.uint8, device="cuda")
+    S.samkv_query_attn_self(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), H.to_dev(ks, dtype),
+                            H.to_dev(vs, dtype), scale, out, lse, ws)
+    heads = list(range(hq)) if hq * lq <= 4096 else [0, 1, hq // 2, hq - 1]
+    G = hq // hkv
+    o_ref = np.empty((len(heads), lq, d))
+    l_ref = np.empty((len(heads), lq))
+    for n, h in enumerate(heads):
+        g = h // G
+        o, l = O.attention_with_self(q[h:h + 1], k[g:g + 1], v[g:g + 1], ks[g:g + 1], vs[g:g + 1], scale)
+        o_ref[n], l_ref[n] = o[0], l[0]
+    H.check_attention(out[heads].cpu().numpy(), lse[heads].cpu().numpy(), o_ref, l_ref, dtype, "query+self")
+    assert torch.isfinite(out).all()

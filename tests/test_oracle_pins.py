@@ -459,3 +459,32 @@ def test_generated_recomputed_rows_have_cosine_near_the_reported_value():
     new = synth.make_recomputed_rows(x.workload, 0, old, x.sigma_k, 0)
     cos = np.einsum("gmc,gmc->gm", new, old) / (np.linalg.norm(new, axis=2) * np.linalg.norm(old, axis=2))
     assert 0.85 < np.median(cos) < 0.95     # Sec. 3.3: the fusion weight is "around 0.9"
+
+
+# ------------------------------------------------------------------ query prefill with its own K/V
+def test_attention_with_self_matches_masked_library_sdpa_and_hand_values():
+    import torch
+    import torch.nn.functional as F
+    r = rng(21)
+    hq, hkv, M, lq, d = 4, 2, 11, 5, 8
+    k_c, v_c = r.standard_normal((hkv, M, d)), r.standard_normal((hkv, M, d))
+    k_s, v_s = r.standard_normal((hkv, lq, d)), r.standard_normal((hkv, lq, d))
+    q = r.standard_normal((hq, lq, d))
+    o, lse = O.attention_with_self(q, k_c, v_c, k_s, v_s, 0.4)
+    kk = torch.from_numpy(np.repeat(np.concatenate([k_c, k_s], axis=1), 2, axis=0))[None]
+    vv = torch.from_numpy(np.repeat(np.concatenate([v_c, v_s], axis=1), 2, axis=0))[None]
+    mask = torch.ones(lq, M + lq, dtype=torch.bool)
+    mask[:, M:] = torch.tril(torch.ones(lq, lq, dtype=torch.bool))
+    ref = F.scaled_dot_product_attention(torch.from_numpy(q)[None], kk, vv, attn_mask=mask, scale=0.4)[0].numpy()
+    assert np.allclose(o, ref, atol=1e-12)
+    # token 0 with an empty... one cached key (logit 0) and its own key (logit ln 3): weights 1/4, 3/4
+    o, lse = O.attention_with_self(np.array([[[1.0]]]), np.array([[[0.0]]]), np.array([[[4.0]]]),
+                                   np.array([[[math.log(3.0)]]]), np.array([[[8.0]]]), 1.0)
+    assert abs(o[0, 0, 0] - 7.0) < 1e-14 and abs(lse[0, 0] - math.log(4.0)) < 1e-14
+    # merging the two partial attentions by log-sum-exp gives the same result (the identity the kernels use)
+    oc, lc = O.attention(q, k_c, v_c, 0.4, False)
+    os_, ls = O.attention(q, k_s, v_s, 0.4, True)
+    o, lse = O.attention_with_self(q, k_c, v_c, k_s, v_s, 0.4)
+    tot = np.logaddexp(lc, ls)
+    assert np.allclose(lse, tot, atol=1e-12)
+    assert np.allclose(o, np.exp(lc - tot)[..., None] * oc + np.exp(ls - tot)[..., None] * os_, atol=1e-12)
