@@ -151,6 +151,9 @@ def at_scale(samkv, iters=5):
                      "TFLOP/s": round(work[name]["flops"] / ms / 1e9, 1),
                      "frac_hbm": round(work[name]["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
                      "frac_mfma": round(work[name]["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    ss_ms = res["score"]["ms"] + res["select"]["ms"]
+    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / ss_ms / 1e6
+    res["score+select"] = {"ms": round(ss_ms, 4), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4)}
     return res
 
 
@@ -256,6 +259,10 @@ def main() -> int:
             peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
             per_kernel[name]["frac_compute"] = round(tfl / peak, 4)
 
+    ss_ms = per_kernel["score"]["ms"] + per_kernel["select"]["ms"]
+    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / (ss_ms * 1e-3) / 1e9
+    per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
+                                  "note": "the two calls as one K-streaming stage: score's bytes + the kept indices"}
     dom = max(KERNELS, key=lambda n: per_kernel[n]["ms"])
     if dom.endswith("attn") and w.dtype == "bf16":
         roof = {"kernel": dom, "bound": "mfma", "achieved": per_kernel[dom]["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
