@@ -251,3 +251,37 @@ def test_gather_q_cache_bit_exact(S, dtype, d):
     q_rec = torch.zeros((8, m, d), dtype=H.torch_dtype(dtype), device="cuda")
     S.samkv_gather_q(caches, q_dev, torch.from_numpy(ref.idx).cuda(), 0.3, q_rec)
     assert np.array_equal(q_rec.float().cpu().numpy(), O.gather_q(q_np, ref.idx, ref.cu_k))
+
+
+def test_hot_path_under_hip_graph_capture_replays_identically(S):
+    """The five calls copy nothing from the host and allocate nothing, so they can be captured into a HIP graph;
+    every replay (with eager work and synchronisations in between) must reproduce the eager results bit for bit."""
+    import torch
+    x = synth.make_small(51, "bf16", [300, 200, 260], 8, 2, 128, 8, 16)
+    w = x.workload
+    caches = H.upload_caches(x)
+    q_tok, q_loc = H.to_dev(x.q_tok, w.dtype), H.to_dev(x.q_loc, w.dtype)
+    ratio, scale = 0.25, 1.0 / math.sqrt(w.head_dim)
+    m = sum(S.samkv_kept_count(n, ratio) for n in x.lens)
+    q_rec = H.to_dev(synth.make_q_rec(w, 0, m), w.dtype)
+    buf = S.alloc_layer_buffers(caches, w.n_q_tok, ratio)
+    S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (buf.scores, buf.idx, buf.k_c, buf.v_c, buf.rec_out, buf.rec_lse, buf.q_out, buf.q_lse)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf)       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf)
+    for rep in range(3):
+        for t in (buf.scores, buf.k_c, buf.v_c, buf.rec_out, buf.rec_lse, buf.q_out, buf.q_lse):
+            t.fill_(float("nan"))                                         # eager work between replays
+        buf.idx.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((buf.scores, buf.idx, buf.k_c, buf.v_c, buf.rec_out, buf.rec_lse, buf.q_out, buf.q_lse), eager):
+            assert torch.equal(got, want), f"replay {rep} differs from the eager run"
