@@ -112,6 +112,33 @@ int samkv_topk_select(const float* scores, const samkv_caches* caches, float rat
                       int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws,
                       size_t ws_bytes, void* stream);
 
+/* Sec. 3.2, dynamic Top-P (Eq. 2 and Eq. 3).  HOST arithmetic on a handful of scalars, no device work:
+ *   P^(n)_i = (s_max - s_anc) / (s_max - s_min)  if s_min < s_anc <= s_max, else 0                  (Eq. 2)
+ *   P_i     = mean over the n_layers stable layers of P^(n)_i                                        (Eq. 3)
+ * s_anc, s_max, s_min: host [n_layers][n_ctx], the scores <Q^_i, K> of document i's anchor block, of its
+ * most-attended and of its least-attended middle block in each stable layer (which blocks those are comes
+ * from the paper's offline attention analysis and is the caller's knowledge; the scores themselves can be
+ * read off samkv_score's output).  p: host [n_ctx], written. */
+int samkv_top_p(const float* s_anc, const float* s_max, const float* s_min, int32_t n_layers, int32_t n_ctx,
+                float* p);
+
+/* Kept tokens of a document of `len` tokens whose n_sink initial and n_local last positions are kept in full
+ * while the middle is sparsified to the share p in [0, 1] (Sec. 3.2: initial and local positions are not
+ * sparsified): n_sink + n_local + ceil(p * (len - n_sink - n_local)), at most len.  0 for invalid arguments. */
+int32_t samkv_kept_count_mid(int32_t len, float p, int32_t n_sink, int32_t n_local);
+
+/* samkv_topk_select with one share per document (the P_i of Eq. 3) applied to the middle segment:
+ * k_i = samkv_kept_count_mid(len[i], p[i], n_sink, n_local).  p: host [n_ctx], each in [0, 1]; a document
+ * may keep nothing, the total must be at least one token.  Everything else as in samkv_topk_select. */
+int samkv_topk_select_v(const float* scores, const samkv_caches* caches, const float* p, int32_t n_sink,
+                        int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws,
+                        size_t ws_bytes, void* stream);
+
+/* samkv_gather with the kept counts given explicitly: cu_k_host is host [n_ctx + 1], the exclusive prefix
+ * sum that the selection returned. */
+int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t* cu_k_host, void* k_c,
+                   void* v_c, void* stream);
+
 /* Sec. 3.2 compaction: K_c[g][cu_k[i] + m][:] = K_i[g][idx[g][cu_k[i] + m]][:], same for V; bit-exact
  * copies.  The kept counts are recomputed from caches->len and `ratio` exactly as in
  * samkv_topk_select, so idx must come from a selection at the same ratio.

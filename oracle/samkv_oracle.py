@@ -12,6 +12,7 @@ the order and notation of the paper:
   local_query          Sec. 3.1 "Add personalized bias": a document's local Q cache as one vector
   personalized_query   Eq. 1: Q^_doc-i = Q_que + 1/(D-1) * sum_{j != i} |cos(Q_que, Q_doc-j_loc)| Q_doc-j_loc
   score                Sec. 3.2 / Table 2: inner product <Q^_doc-i, K>
+  top_p                Sec. 3.2, Eq. 2 and Eq. 3: dynamic share per document from anchor / max / min block scores
   kept_count           budget ratio -> number of kept tokens per document and head
   select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
   gather, gather_q     Sec. 3.2: concatenate the kept K/V (and stored Q) of all documents in their original order
@@ -116,6 +117,50 @@ def kept_count(length: int, ratio: float) -> int:
     0.1 * 20, is not pushed up by the float32 rounding of the ratio."""
     r = float(np.float32(ratio))
     return int(min(length, max(1, math.ceil(r * length * (1.0 - 2.0 ** -22)))))
+
+
+def top_p(s_anc: np.ndarray, s_max: np.ndarray, s_min: np.ndarray) -> np.ndarray:
+    """Dynamic Top-P of Sec. 3.2.  Inputs [n_layers, n_ctx]: per stable layer and document the scores of the
+    anchor block, of the most-attended and of the least-attended middle block.
+
+    Eq. 2: P^(n)_i = (s_max - s_anc) / (s_max - s_min) if s_anc lies in (s_min, s_max], otherwise 0.
+    Eq. 3: P_i = mean of P^(n)_i over the layers.  Returns [n_ctx]."""
+    s_anc, s_max, s_min = (np.asarray(a, F64) for a in (s_anc, s_max, s_min))
+    n_layers, n_ctx = s_anc.shape
+    p = np.zeros(n_ctx, F64)
+    for i in range(n_ctx):
+        for n in range(n_layers):
+            if s_min[n, i] < s_anc[n, i] <= s_max[n, i]:
+                p[i] += (s_max[n, i] - s_anc[n, i]) / (s_max[n, i] - s_min[n, i])
+        p[i] /= n_layers
+    return p
+
+
+def kept_count_mid(length: int, p: float, n_sink: int, n_local: int) -> int:
+    """Kept tokens when the n_sink initial and n_local last positions are kept in full and the middle segment is
+    sparsified to the share p (Sec. 3.2): forced + ceil(p * middle), with the float32 guard of kept_count."""
+    forced = n_sink + n_local
+    if forced >= length:
+        return length
+    mid = length - forced
+    k = math.ceil(float(np.float32(p)) * mid * (1.0 - 2.0 ** -22))
+    return forced + int(min(mid, max(0, k)))
+
+
+def select_v(scores: Sequence[np.ndarray], p: Sequence[float], n_sink: int = 0, n_local: int = 0
+             ) -> Tuple[np.ndarray, np.ndarray]:
+    """As select, with one middle-segment share per document (the P_i of Eq. 3)."""
+    hkv = scores[0].shape[0]
+    ks = [kept_count_mid(s.shape[1], pi, n_sink, n_local) for s, pi in zip(scores, p)]
+    cu_k = np.concatenate([[0], np.cumsum(ks)]).astype(np.int32)
+    idx = np.empty((hkv, int(cu_k[-1])), np.int32)
+    for i, s in enumerate(scores):
+        if ks[i] == 0:
+            continue
+        L = s.shape[1]
+        for g in range(hkv):
+            idx[g, cu_k[i]:cu_k[i + 1]] = select_row(np.asarray(s[g], F64), ks[i], min(n_sink, L), min(n_local, max(0, L - n_sink)))
+    return idx, cu_k
 
 
 def select_row(scores: np.ndarray, k: int, n_sink: int = 0, n_local: int = 0) -> np.ndarray:

@@ -51,6 +51,30 @@ int check_caches(const samkv_caches* c, bool need_k, bool need_v, Shape* s) {
   return SAMKV_OK;
 }
 
+// Kept tokens of a document whose middle segment (everything but the forced initial and local positions)
+// is sparsified to the share p in [0, 1]: forced + ceil(p * middle), with the same float32 guard as above.
+int kept_count_mid(int len, float p, int n_sink, int n_local) {
+  if (len < 1 || !(p >= 0.f) || p > 1.f || n_sink < 0 || n_local < 0) return -1;
+  const long long forced = (long long)n_sink + n_local;
+  if (forced >= len) return len;
+  const long long mid = len - forced;
+  long long k = (long long)ceil((double)p * (double)mid * (1.0 - 0x1p-22));
+  if (k < 0) k = 0;
+  if (k > mid) k = mid;
+  return (int)(forced + k);
+}
+
+int kept_table_mid(const samkv_caches* c, const float* p, int n_sink, int n_local, IntTable* cu_k) {
+  if (p == nullptr) return SAMKV_EINVAL;
+  cu_k->v[0] = 0;
+  for (int i = 0; i < c->n_ctx; ++i) {
+    const int k = kept_count_mid(c->len[i], p[i], n_sink, n_local);
+    if (k < 0) return SAMKV_EINVAL;
+    cu_k->v[i + 1] = cu_k->v[i] + k;
+  }
+  return cu_k->v[c->n_ctx] >= 1 ? SAMKV_OK : SAMKV_EINVAL;
+}
+
 int kept_table(const samkv_caches* c, float ratio, int n_sink, int n_local, IntTable* cu_k) {
   if (!(ratio > 0.f) || ratio > 1.f || n_sink < 0 || n_local < 0) return SAMKV_EINVAL;
   cu_k->v[0] = 0;
@@ -185,6 +209,43 @@ int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, 
   return dev(launch_score(a, kt, s.cu_len, static_cast<hipStream_t>(stream)));
 }
 
+static int select_common(const float* scores, const samkv_caches* caches, const Shape& s, const IntTable& cu_k,
+                         int32_t n_sink, int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host,
+                         void* stream);
+
+int32_t samkv_kept_count_mid(int32_t len, float p, int32_t n_sink, int32_t n_local) {
+  const int k = kept_count_mid(len, p, n_sink, n_local);
+  return k < 0 ? 0 : k;
+}
+
+int samkv_top_p(const float* s_anc, const float* s_max, const float* s_min, int32_t n_layers, int32_t n_ctx, float* p) {
+  if (s_anc == nullptr || s_max == nullptr || s_min == nullptr || p == nullptr || n_layers < 1 || n_ctx < 1)
+    return SAMKV_EINVAL;
+  for (int i = 0; i < n_ctx; ++i) {
+    double acc = 0.0;
+    for (int n = 0; n < n_layers; ++n) {
+      const double a = s_anc[(size_t)n * n_ctx + i], hi = s_max[(size_t)n * n_ctx + i], lo = s_min[(size_t)n * n_ctx + i];
+      if (a > lo && a <= hi) acc += (hi - a) / (hi - lo);   // Eq. 2; 0 otherwise
+    }
+    p[i] = (float)(acc / n_layers);                          // Eq. 3
+  }
+  return SAMKV_OK;
+}
+
+int samkv_topk_select_v(const float* scores, const samkv_caches* caches, const float* p, int32_t n_sink,
+                        int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws, size_t ws_bytes,
+                        void* stream) {
+  (void)ws; (void)ws_bytes;
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (scores == nullptr || idx == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table_mid(caches, p, n_sink, n_local, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  return select_common(scores, caches, s, cu_k, n_sink, n_local, idx, cu_k_dev, cu_k_host, stream);
+}
+
 int samkv_topk_select(const float* scores, const samkv_caches* caches, float ratio, int32_t n_sink, int32_t n_local,
                       int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
   (void)ws; (void)ws_bytes;
@@ -195,12 +256,39 @@ int samkv_topk_select(const float* scores, const samkv_caches* caches, float rat
   IntTable cu_k;
   rc = kept_table(caches, ratio, n_sink, n_local, &cu_k);
   if (rc != SAMKV_OK) return rc;
+  return select_common(scores, caches, s, cu_k, n_sink, n_local, idx, cu_k_dev, cu_k_host, stream);
+}
+
+static int select_common(const float* scores, const samkv_caches* caches, const Shape& s, const IntTable& cu_k,
+                         int32_t n_sink, int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host,
+                         void* stream) {
+  (void)caches;
   if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
   SelectLaunch a;
   a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.max_len = s.max_len; a.total_len = s.total_len;
   a.m_total = cu_k.v[s.n_ctx]; a.n_sink = n_sink; a.n_local = n_local;
   a.scores = scores; a.idx = idx; a.cu_k_dev = cu_k_dev;
   return dev(launch_select(a, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
+}
+
+static int gather_common(const samkv_caches* caches, const Shape& s, const IntTable& cu_k, const int32_t* idx,
+                         void* k_c, void* v_c, void* stream);
+
+int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t* cu_k_host, void* k_c, void* v_c,
+                   void* stream) {
+  Shape s;
+  int rc = check_caches(caches, true, true, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (idx == nullptr || k_c == nullptr || v_c == nullptr || cu_k_host == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  if (cu_k_host[0] != 0) return SAMKV_EINVAL;
+  for (int i = 0; i < s.n_ctx; ++i) {
+    const int k = cu_k_host[i + 1] - cu_k_host[i];
+    if (k < 0 || k > caches->len[i]) return SAMKV_EINVAL;
+  }
+  if (cu_k_host[s.n_ctx] < 1) return SAMKV_EINVAL;
+  memcpy(cu_k.v, cu_k_host, sizeof(int32_t) * (s.n_ctx + 1));
+  return gather_common(caches, s, cu_k, idx, k_c, v_c, stream);
 }
 
 int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, void* k_c, void* v_c, void* stream) {
@@ -211,6 +299,11 @@ int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, vo
   IntTable cu_k;
   rc = kept_table(caches, ratio, 0, 0, &cu_k);
   if (rc != SAMKV_OK) return rc;
+  return gather_common(caches, s, cu_k, idx, k_c, v_c, stream);
+}
+
+static int gather_common(const samkv_caches* caches, const Shape& s, const IntTable& cu_k, const int32_t* idx,
+                         void* k_c, void* v_c, void* stream) {
   PtrTable kt, vt;
   memset(&kt, 0, sizeof(kt));
   memset(&vt, 0, sizeof(vt));

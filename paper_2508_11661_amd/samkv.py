@@ -17,7 +17,8 @@ SAMKV_F32, SAMKV_BF16 = 0, 1
 SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
-EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_workspace_bytes", "samkv_score", "samkv_topk_select",
+EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
+           "samkv_score", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
            "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
@@ -50,6 +51,14 @@ def _load() -> ctypes.CDLL:
     lib.samkv_topk_select.argtypes = [vp, cp, f32, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_gather.restype = ctypes.c_int
     lib.samkv_gather.argtypes = [cp, vp, f32, vp, vp, vp]
+    lib.samkv_kept_count_mid.restype = i32
+    lib.samkv_kept_count_mid.argtypes = [i32, f32, i32, i32]
+    lib.samkv_top_p.restype = ctypes.c_int
+    lib.samkv_top_p.argtypes = [ctypes.POINTER(f32)] * 3 + [i32, i32, ctypes.POINTER(f32)]
+    lib.samkv_topk_select_v.restype = ctypes.c_int
+    lib.samkv_topk_select_v.argtypes = [vp, cp, ctypes.POINTER(f32), i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.samkv_gather_v.restype = ctypes.c_int
+    lib.samkv_gather_v.argtypes = [cp, vp, ctypes.POINTER(i32), vp, vp, vp]
     lib.samkv_gather_q.restype = ctypes.c_int
     lib.samkv_gather_q.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, f32, vp, vp]
     lib.samkv_recompute_attn.restype = ctypes.c_int
@@ -162,6 +171,34 @@ def samkv_topk_select(scores: torch.Tensor, caches: Caches, ratio: float, n_sink
                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
            "samkv_topk_select")
     return list(cu_k_host)
+
+
+def samkv_kept_count_mid(length: int, p: float, n_sink: int, n_local: int) -> int:
+    return int(_lib.samkv_kept_count_mid(length, p, n_sink, n_local))
+
+
+def samkv_top_p(s_anc, s_max, s_min) -> List[float]:
+    """Eq. 2 and Eq. 3 on host arrays [n_layers][n_ctx] -> P_i per document."""
+    n_layers, n_ctx = len(s_anc), len(s_anc[0])
+    flat = lambda a: (ctypes.c_float * (n_layers * n_ctx))(*[float(x) for row in a for x in row])
+    out = (ctypes.c_float * n_ctx)()
+    _check(_lib.samkv_top_p(flat(s_anc), flat(s_max), flat(s_min), n_layers, n_ctx, out), "samkv_top_p")
+    return list(out)
+
+
+def samkv_topk_select_v(scores: torch.Tensor, caches: Caches, p: Sequence[float], n_sink: int, n_local: int,
+                        idx: torch.Tensor, cu_k_dev: Optional[torch.Tensor]) -> List[int]:
+    """Selection with one middle-segment share per document; returns the host prefix sums cu_k."""
+    cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
+    pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    _check(_lib.samkv_topk_select_v(_ptr(scores), ctypes.byref(caches.c), pp, n_sink, n_local, _ptr(idx),
+                                    _ptr(cu_k_dev), cu_k_host, None, 0, _stream()), "samkv_topk_select_v")
+    return list(cu_k_host)
+
+
+def samkv_gather_v(caches: Caches, idx: torch.Tensor, cu_k: Sequence[int], k_c: torch.Tensor, v_c: torch.Tensor) -> None:
+    cu = (ctypes.c_int32 * (caches.n_ctx + 1))(*[int(x) for x in cu_k])
+    _check(_lib.samkv_gather_v(ctypes.byref(caches.c), _ptr(idx), cu, _ptr(k_c), _ptr(v_c), _stream()), "samkv_gather_v")
 
 
 def samkv_gather(caches: Caches, idx: torch.Tensor, ratio: float, k_c: torch.Tensor, v_c: torch.Tensor) -> None:

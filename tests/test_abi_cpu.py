@@ -43,6 +43,21 @@ def test_kept_count_matches_oracle_definition(S):
     assert S.samkv_kept_count(0, 0.5) == 0 and S.samkv_kept_count(10, 0.0) == 0 and S.samkv_kept_count(10, 1.5) == 0
 
 
+def test_top_p_and_mid_counts_match_oracle(S):
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        n_layers, n_ctx = int(rng.integers(1, 6)), int(rng.integers(1, 9))
+        mn = rng.standard_normal((n_layers, n_ctx)).astype(np.float32)
+        mx = mn + np.abs(rng.standard_normal((n_layers, n_ctx))).astype(np.float32)
+        anc = (mn + rng.uniform(-0.3, 1.3, size=(n_layers, n_ctx)) * (mx - mn)).astype(np.float32)
+        got = S.samkv_top_p(anc.tolist(), mx.tolist(), mn.tolist())
+        assert np.allclose(got, O.top_p(anc, mx, mn), rtol=1e-6, atol=1e-7)
+    assert S.samkv_top_p([[4.0, 10.0, 0.0]], [[10.0, 10.0, 10.0]], [[0.0, 0.0, 0.0]]) == pytest.approx([0.6, 0.0, 0.0])
+    for L, p, a, b in [(1000, 0.0, 64, 128), (1000, 1.0, 64, 128), (1000, 0.25, 64, 128), (100, 0.5, 64, 128),
+                       (20, 0.1, 0, 0), (20, 0.0, 0, 0), (4096, 0.149, 64, 128), (7, 0.33, 1, 1)]:
+        assert S.samkv_kept_count_mid(L, p, a, b) == O.kept_count_mid(L, p, a, b), (L, p, a, b)
+
+
 def test_workspace_bytes(S):
     assert S.samkv_workspace_bytes(10, 32, 8, 128, 32, 1540) > 0
     assert S.samkv_workspace_bytes(0, 32, 8, 128, 32, 1540) == 0

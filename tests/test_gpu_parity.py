@@ -285,3 +285,27 @@ def test_hot_path_under_hip_graph_capture_replays_identically(S):
         torch.cuda.synchronize()
         for got, want in zip((buf.scores, buf.idx, buf.k_c, buf.v_c, buf.rec_out, buf.rec_lse, buf.q_out, buf.q_lse), eager):
             assert torch.equal(got, want), f"replay {rep} differs from the eager run"
+
+
+def test_select_with_per_document_top_p_and_explicit_gather(S):
+    """Eq. 3's P_i per document on the middle segment, forced initial/local positions, a document that keeps only
+    its forced positions and one that keeps nothing at all; gather with the explicit prefix sums."""
+    import torch
+    x = synth.make_small(61, "bf16", [700, 130, 64, 1500, 33], 8, 2, 128, 4, 8)
+    n = len(x.k)
+    scores32 = [s.astype(np.float32) for s in O.score(O.personalized_query(x.q_tok, x.q_loc, n), x.k)]
+    caches = H.upload_caches(x)
+    dev_scores = torch.from_numpy(np.concatenate(scores32, axis=1)).cuda()
+    for p, n_sink, n_local in (([0.15, 0.5, 0.0, 0.07, 1.0], 8, 16), ([0.3, 0.0, 0.0, 0.2, 0.0], 0, 0)):
+        want, cu = O.select_v([s.astype(np.float64) for s in scores32], p, n_sink, n_local)
+        m = int(cu[-1])
+        idx = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+        cu_dev = torch.zeros((n + 1,), dtype=torch.int32, device="cuda")
+        got_cu = S.samkv_topk_select_v(dev_scores, caches, p, n_sink, n_local, idx, cu_dev)
+        assert got_cu == cu.tolist() == cu_dev.cpu().tolist()
+        assert np.array_equal(idx.cpu().numpy(), want)
+        k_c = torch.zeros((2, m, 128), dtype=torch.bfloat16, device="cuda")
+        v_c = torch.zeros_like(k_c)
+        S.samkv_gather_v(caches, idx, got_cu, k_c, v_c)
+        k_ref, v_ref = O.gather(x.k, x.v, want, cu)
+        assert np.array_equal(k_c.float().cpu().numpy(), k_ref) and np.array_equal(v_c.float().cpu().numpy(), v_ref)

@@ -488,3 +488,47 @@ def test_attention_with_self_matches_masked_library_sdpa_and_hand_values():
     tot = np.logaddexp(lc, ls)
     assert np.allclose(lse, tot, atol=1e-12)
     assert np.allclose(o, np.exp(lc - tot)[..., None] * oc + np.exp(ls - tot)[..., None] * os_, atol=1e-12)
+
+
+# ------------------------------------------------------------------ dynamic Top-P (Eq. 2, Eq. 3)
+def test_top_p_hand_values_and_edge_cases():
+    # one layer, five documents: (anc, max, min)
+    #   (4, 10, 0)  -> (10 - 4) / (10 - 0) = 0.6
+    #   (10, 10, 0) -> anchor equals max: inside (min, max], numerator 0 -> 0
+    #   (0, 10, 0)  -> anchor equals min: outside the half-open interval -> 0
+    #   (12, 10, 0) -> anchor above max -> 0
+    #   (5, 5, 5)   -> empty interval -> 0
+    anc = np.array([[4.0, 10.0, 0.0, 12.0, 5.0]])
+    mx = np.array([[10.0, 10.0, 10.0, 10.0, 5.0]])
+    mn = np.array([[0.0, 0.0, 0.0, 0.0, 5.0]])
+    assert np.allclose(O.top_p(anc, mx, mn), [0.6, 0.0, 0.0, 0.0, 0.0], atol=1e-15)
+    # Eq. 3: mean over layers; 0.6 and 0.2 -> 0.4; a layer that falls in the "otherwise" branch counts as 0
+    anc = np.array([[4.0], [8.0], [11.0]])
+    mx = np.array([[10.0], [10.0], [10.0]])
+    mn = np.array([[0.0], [0.0], [0.0]])
+    assert np.allclose(O.top_p(anc[:2], mx[:2], mn[:2]), [0.4], atol=1e-15)
+    assert np.allclose(O.top_p(anc, mx, mn), [0.8 / 3.0], atol=1e-15)
+    # the direction the paper argues for: P grows with s_max, shrinks with s_anc and with s_min
+    base = O.top_p([[4.0]], [[10.0]], [[0.0]])[0]
+    assert O.top_p([[4.0]], [[12.0]], [[0.0]])[0] > base
+    assert O.top_p([[5.0]], [[10.0]], [[0.0]])[0] < base
+    assert O.top_p([[4.0]], [[10.0]], [[1.0]])[0] > base - 1.0 and O.top_p([[4.0]], [[10.0]], [[-5.0]])[0] < base
+
+
+def test_kept_count_mid_and_select_v():
+    assert O.kept_count_mid(1000, 0.0, 64, 128) == 192
+    assert O.kept_count_mid(1000, 1.0, 64, 128) == 1000
+    assert O.kept_count_mid(1000, 0.25, 64, 128) == 192 + 202          # ceil(0.25 * 808)
+    assert O.kept_count_mid(100, 0.5, 64, 128) == 100                  # forced positions cover the document
+    assert O.kept_count_mid(20, 0.1, 0, 0) == 2 and O.kept_count_mid(20, 0.0, 0, 0) == 0
+    r = rng(22)
+    scores = [r.standard_normal((2, L)) for L in (30, 12, 50)]
+    idx, cu = O.select_v(scores, [0.2, 0.0, 0.5], n_sink=2, n_local=3)
+    assert list(cu) == [0, 5 + 5, 10 + 5, 15 + 5 + 23]                 # forced 5 each + ceil(0.2*25)=5, 0, ceil(0.5*45)=23
+    for g in range(2):
+        seg = idx[g, :10]
+        assert set([0, 1, 27, 28, 29]) <= set(seg.tolist())
+        mid = [p for p in seg if 2 <= p < 27]
+        best = np.argsort(-scores[0][g, 2:27], kind="stable")[:5] + 2
+        assert sorted(mid) == sorted(best.tolist())
+        assert idx[g, 10:15].tolist() == [0, 1, 9, 10, 11]             # a document with P = 0 keeps only the forced ones
