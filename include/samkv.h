@@ -134,6 +134,35 @@ int samkv_topk_select_v(const float* scores, const samkv_caches* caches, const f
                         int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws,
                         size_t ws_bytes, void* stream);
 
+/* Sec. 3.2, block-level retrieval: the cache is managed in blocks of `block` consecutive tokens and a block is
+ * represented by the mean of its keys (Setup: 64-token blocks).  The inner product is linear, so the score of a
+ * block is the mean of its tokens' scores:
+ *   bscores[g][cu_b[i] + b] = mean over t in [b*block, min(len[i], (b+1)*block)) of scores[g][cu_len[i] + t]
+ * with cu_b the exclusive prefix sum of ceil(len[i] / block); a document's last block may be short.
+ *   scores   [Hkv][sum len] float32 (samkv_score's output);   bscores [Hkv][sum ceil(len/block)] float32 written
+ *   1 <= block <= 4096.   caches->k and caches->v are not read. */
+int samkv_block_scores(const float* scores, const samkv_caches* caches, int32_t block, float* bscores,
+                       void* stream);
+
+/* Workspace of samkv_block_select, bytes (0 for invalid arguments). */
+size_t samkv_block_workspace_bytes(const samkv_caches* caches, int32_t block);
+
+/* Sec. 3.2 selection at block granularity.  Per document i and KV head g: the first n_init_blocks and the last
+ * n_local_blocks blocks are always kept (Setup: 1 and 2), and of the B_i - n_init_blocks - n_local_blocks middle
+ * blocks the ceil(p[i] * middle) with the largest block scores (ties to the lower block).  The kept blocks are
+ * written out as the positions of their tokens, so the result feeds samkv_gather_v / samkv_gather_q unchanged:
+ *   idx        [Hkv][M] int32 written: document-local token positions, ascending inside each document
+ *   cu_k_dev / cu_k_host   [n_ctx + 1] exclusive prefix sum of the kept TOKENS per document (either may be NULL)
+ *   p          host [n_ctx], each in [0, 1] (the P_i of Eq. 3)
+ * Every head must keep the same number of tokens, so a short last block has to be kept by all heads or by none:
+ * with n_local_blocks == 0 a document whose length is not a multiple of `block` is SAMKV_EINVAL unless it keeps
+ * all of its blocks or none.  ws: samkv_block_workspace_bytes(caches, block) bytes, 256-byte aligned.
+ * The second, cross-document filter that the paper applies to the retrieved blocks is not part of this call:
+ * the paper does not define the normalisation it compares blocks of different documents under. */
+int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t block, const float* p,
+                       int32_t n_init_blocks, int32_t n_local_blocks, int32_t* idx, int32_t* cu_k_dev,
+                       int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream);
+
 /* samkv_gather with the kept counts given explicitly: cu_k_host is host [n_ctx + 1], the exclusive prefix
  * sum that the selection returned. */
 int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t* cu_k_host, void* k_c,
@@ -154,6 +183,10 @@ int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, vo
  *   q_rec    [Hq][M][d] written.   caches->k and caches->v are not read. */
 int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx, float ratio,
                    void* q_rec, void* stream);
+
+/* samkv_gather_q with the kept counts given explicitly (cu_k_host as in samkv_gather_v). */
+int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx,
+                     const int32_t* cu_k_host, void* q_rec, void* stream);
 
 /* Sec. 3.3 recomputation, attention part.  Row p of query head h is the query state of the token
  * that KV head g(h) keeps at compacted position p; it attends to compacted positions 0..p (itself

@@ -15,6 +15,7 @@ the order and notation of the paper:
   top_p                Sec. 3.2, Eq. 2 and Eq. 3: dynamic share per document from anchor / max / min block scores
   kept_count           budget ratio -> number of kept tokens per document and head
   select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
+  block_scores / block_select   Sec. 3.2 block-level retrieval: mean-key block representatives, forced blocks
   gather, gather_q     Sec. 3.2: concatenate the kept K/V (and stored Q) of all documents in their original order
   kv_update            Sec. 3.3, Eq. 4: overwrite or cosine-weighted fusion of recomputed K/V rows
   attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
@@ -190,6 +191,53 @@ def select(scores: Sequence[np.ndarray], ratio: float, n_sink: int = 0, n_local:
         for g in range(hkv):
             idx[g, cu_k[i]:cu_k[i + 1]] = select_row(np.asarray(s[g], F64), ks[i], n_sink, n_local)
     return idx, cu_k
+
+
+def block_scores(q_hat: np.ndarray, k: Sequence[np.ndarray], block: int) -> List[np.ndarray]:
+    """Block-level retrieval of Sec. 3.2: a block of `block` consecutive tokens is represented by the mean of its
+    keys and scored like a token, b[i][g, n] = (1/G) * sum_{h in group g} <Q^_i[h], mean_t K_i[g, t, :]>, t over
+    block n (the last block of a document may be short).  Returns one [Hkv, ceil(L_i / block)] array per document."""
+    reps = []
+    for ki in k:
+        ki = np.asarray(ki, F64)
+        hkv, L, d = ki.shape
+        nb = -(-L // block)
+        rep = np.zeros((hkv, nb, d), F64)
+        for n in range(nb):
+            rep[:, n, :] = ki[:, n * block:min(L, (n + 1) * block), :].mean(axis=1)
+        reps.append(rep)
+    return score(q_hat, reps)
+
+
+def block_select(bscores: Sequence[np.ndarray], lens: Sequence[int], block: int, p: Sequence[float],
+                 n_init_blocks: int = 1, n_local_blocks: int = 2) -> Tuple[np.ndarray, np.ndarray]:
+    """Selection at block granularity (Sec. 3.2; Setup: the initial block and the last two are always kept).
+
+    Per document and KV head the forced blocks are kept, and of the middle blocks the share p[i] with the largest
+    block scores; the kept blocks are returned as the positions of their tokens: idx [Hkv, M] and cu_k [N+1]
+    counting tokens.  Requires that every head keeps the same number of tokens (true when the short last block
+    is forced, or when no block is short)."""
+    hkv = bscores[0].shape[0]
+    rows: List[List[np.ndarray]] = [[] for _ in range(hkv)]
+    cu_k = [0]
+    for i, (b, L) in enumerate(zip(bscores, lens)):
+        nb = b.shape[1]
+        assert nb == -(-L // block)
+        kb = kept_count_mid(nb, p[i], n_init_blocks, n_local_blocks)
+        n_tok = None
+        for g in range(hkv):
+            if kb == 0:
+                toks = np.zeros(0, np.int32)
+            else:
+                ni = min(n_init_blocks, nb)
+                blocks = select_row(np.asarray(b[g], F64), kb, ni, min(n_local_blocks, nb - ni))
+                toks = np.concatenate([np.arange(n * block, min(L, (n + 1) * block)) for n in blocks]).astype(np.int32)
+            assert n_tok is None or n_tok == toks.shape[0], "heads keep different numbers of tokens"
+            n_tok = toks.shape[0]
+            rows[g].append(toks)
+        cu_k.append(cu_k[-1] + n_tok)
+    idx = np.stack([np.concatenate(r) for r in rows]).astype(np.int32)
+    return idx, np.asarray(cu_k, np.int32)
 
 
 # --------------------------------------------------------------------------- compaction

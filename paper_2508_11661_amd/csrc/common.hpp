@@ -51,6 +51,11 @@ struct SelectLaunch {
 };
 hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s);
 
+hipError_t launch_block_scores(const float* scores, const IntTable& cu_len, const IntTable& cu_blk, int n_ctx, int hkv,
+                               int total_len, int block, float* bscores, hipStream_t s);
+hipError_t launch_expand_blocks(const int32_t* bidx, const IntTable& cu_len, const IntTable& cu_kb, const IntTable& cu_k,
+                                int n_ctx, int hkv, int block, int32_t* idx, int32_t* cu_k_dev, hipStream_t s);
+
 struct GatherLaunch {
   int n_ctx, hkv, row_bytes, m_total, max_k;
   const int32_t* idx;

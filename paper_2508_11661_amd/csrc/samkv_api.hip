@@ -271,23 +271,87 @@ static int select_common(const float* scores, const samkv_caches* caches, const 
   return dev(launch_select(a, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
 }
 
+// ---- block-granular selection (Sec. 3.2: blocks of tokens represented by their mean key) -----------------
+static int block_table(const samkv_caches* caches, const Shape& s, int block, IntTable* cu_blk) {
+  if (block < 1 || block > 4096) return SAMKV_EINVAL;
+  cu_blk->v[0] = 0;
+  for (int i = 0; i < s.n_ctx; ++i) cu_blk->v[i + 1] = cu_blk->v[i] + (caches->len[i] + block - 1) / block;
+  return SAMKV_OK;
+}
+
+size_t samkv_block_workspace_bytes(const samkv_caches* caches, int32_t block) {
+  Shape s;
+  IntTable cu_blk;
+  if (check_caches(caches, false, false, &s) != SAMKV_OK || block_table(caches, s, block, &cu_blk) != SAMKV_OK) return 0;
+  return align_up((size_t)s.hkv * cu_blk.v[s.n_ctx] * 4) + kAlign;
+}
+
+int samkv_block_scores(const float* scores, const samkv_caches* caches, int32_t block, float* bscores, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (scores == nullptr || bscores == nullptr) return SAMKV_EINVAL;
+  IntTable cu_blk;
+  rc = block_table(caches, s, block, &cu_blk);
+  if (rc != SAMKV_OK) return rc;
+  return dev(launch_block_scores(scores, s.cu_len, cu_blk, s.n_ctx, s.hkv, s.total_len, block, bscores,
+                                 static_cast<hipStream_t>(stream)));
+}
+
+int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t block, const float* p,
+                       int32_t n_init_blocks, int32_t n_local_blocks, int32_t* idx, int32_t* cu_k_dev,
+                       int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (bscores == nullptr || idx == nullptr || p == nullptr || n_init_blocks < 0 || n_local_blocks < 0) return SAMKV_EINVAL;
+  IntTable cu_blk, cu_kb, cu_k;
+  rc = block_table(caches, s, block, &cu_blk);
+  if (rc != SAMKV_OK) return rc;
+  cu_kb.v[0] = 0;
+  cu_k.v[0] = 0;
+  int max_nb = 0;
+  for (int i = 0; i < s.n_ctx; ++i) {
+    const int L = caches->len[i], nb = cu_blk.v[i + 1] - cu_blk.v[i];
+    const int kb = kept_count_mid(nb, p[i], n_init_blocks, n_local_blocks);
+    if (kb < 0) return SAMKV_EINVAL;
+    const bool short_last = L % block != 0;
+    // a short last block must be kept by every head or by none: it is kept whenever local blocks are forced
+    if (short_last && n_local_blocks == 0 && kb != 0 && kb != nb) return SAMKV_EINVAL;
+    const bool last_kept = kb == nb || (n_local_blocks > 0 && kb > 0);
+    const int tokens = kb * block - ((last_kept && short_last) ? (block - L % block) : 0);
+    cu_kb.v[i + 1] = cu_kb.v[i] + kb;
+    cu_k.v[i + 1] = cu_k.v[i] + tokens;
+    if (nb > max_nb) max_nb = nb;
+  }
+  if (cu_k.v[s.n_ctx] < 1) return SAMKV_EINVAL;
+  const size_t need = align_up((size_t)s.hkv * cu_blk.v[s.n_ctx] * 4);
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return SAMKV_EWORKSPACE;
+  if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
+  int32_t* bidx = static_cast<int32_t*>(ws);
+  SelectLaunch a;
+  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.max_len = max_nb; a.total_len = cu_blk.v[s.n_ctx];
+  a.m_total = cu_kb.v[s.n_ctx]; a.n_sink = n_init_blocks; a.n_local = n_local_blocks;
+  a.scores = bscores; a.idx = bidx; a.cu_k_dev = nullptr;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_select(a, cu_blk, cu_kb, st);
+  if (e == hipSuccess) e = launch_expand_blocks(bidx, s.cu_len, cu_kb, cu_k, s.n_ctx, s.hkv, block, idx, cu_k_dev, st);
+  return dev(e);
+}
+
 static int gather_common(const samkv_caches* caches, const Shape& s, const IntTable& cu_k, const int32_t* idx,
                          void* k_c, void* v_c, void* stream);
+static int checked_cu_k(const samkv_caches* caches, const Shape& s, const int32_t* cu_k_host, IntTable* cu_k);
 
 int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t* cu_k_host, void* k_c, void* v_c,
                    void* stream) {
   Shape s;
   int rc = check_caches(caches, true, true, &s);
   if (rc != SAMKV_OK) return rc;
-  if (idx == nullptr || k_c == nullptr || v_c == nullptr || cu_k_host == nullptr) return SAMKV_EINVAL;
+  if (idx == nullptr || k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
   IntTable cu_k;
-  if (cu_k_host[0] != 0) return SAMKV_EINVAL;
-  for (int i = 0; i < s.n_ctx; ++i) {
-    const int k = cu_k_host[i + 1] - cu_k_host[i];
-    if (k < 0 || k > caches->len[i]) return SAMKV_EINVAL;
-  }
-  if (cu_k_host[s.n_ctx] < 1) return SAMKV_EINVAL;
-  memcpy(cu_k.v, cu_k_host, sizeof(int32_t) * (s.n_ctx + 1));
+  rc = checked_cu_k(caches, s, cu_k_host, &cu_k);
+  if (rc != SAMKV_OK) return rc;
   return gather_common(caches, s, cu_k, idx, k_c, v_c, stream);
 }
 
@@ -316,15 +380,19 @@ static int gather_common(const samkv_caches* caches, const Shape& s, const IntTa
   return dev(launch_gather(a, kt, vt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
 }
 
-int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx, float ratio, void* q_rec,
-                   void* stream) {
-  Shape s;
-  int rc = check_caches(caches, false, false, &s);
-  if (rc != SAMKV_OK) return rc;
-  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
-  IntTable cu_k;
-  rc = kept_table(caches, ratio, 0, 0, &cu_k);
-  if (rc != SAMKV_OK) return rc;
+static int checked_cu_k(const samkv_caches* caches, const Shape& s, const int32_t* cu_k_host, IntTable* cu_k) {
+  if (cu_k_host == nullptr || cu_k_host[0] != 0) return SAMKV_EINVAL;
+  for (int i = 0; i < s.n_ctx; ++i) {
+    const int k = cu_k_host[i + 1] - cu_k_host[i];
+    if (k < 0 || k > caches->len[i]) return SAMKV_EINVAL;
+  }
+  if (cu_k_host[s.n_ctx] < 1) return SAMKV_EINVAL;
+  memcpy(cu_k->v, cu_k_host, sizeof(int32_t) * (s.n_ctx + 1));
+  return SAMKV_OK;
+}
+
+static int gather_q_common(const samkv_caches* caches, const Shape& s, const IntTable& cu_k, const void* const* q_cache,
+                           const int32_t* idx, void* q_rec, void* stream) {
   PtrTable qt;
   memset(&qt, 0, sizeof(qt));
   for (int i = 0; i < s.n_ctx; ++i) {
@@ -337,6 +405,30 @@ int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const
   a.max_k = 0;
   for (int i = 0; i < s.n_ctx; ++i) a.max_k = cu_k.v[i + 1] - cu_k.v[i] > a.max_k ? cu_k.v[i + 1] - cu_k.v[i] : a.max_k;
   return dev(launch_gather_q(a, qt, s.cu_len, cu_k, s.hq, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx, float ratio, void* q_rec,
+                   void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table(caches, ratio, 0, 0, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  return gather_q_common(caches, s, cu_k, q_cache, idx, q_rec, stream);
+}
+
+int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, const int32_t* idx,
+                     const int32_t* cu_k_host, void* q_rec, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = checked_cu_k(caches, s, cu_k_host, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  return gather_q_common(caches, s, cu_k, q_cache, idx, q_rec, stream);
 }
 
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,

@@ -19,6 +19,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
            "samkv_score", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
+           "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
            "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
@@ -59,6 +60,14 @@ def _load() -> ctypes.CDLL:
     lib.samkv_topk_select_v.argtypes = [vp, cp, ctypes.POINTER(f32), i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_gather_v.restype = ctypes.c_int
     lib.samkv_gather_v.argtypes = [cp, vp, ctypes.POINTER(i32), vp, vp, vp]
+    lib.samkv_gather_q_v.restype = ctypes.c_int
+    lib.samkv_gather_q_v.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, ctypes.POINTER(i32), vp, vp]
+    lib.samkv_block_scores.restype = ctypes.c_int
+    lib.samkv_block_scores.argtypes = [vp, cp, i32, vp, vp]
+    lib.samkv_block_workspace_bytes.restype = sz
+    lib.samkv_block_workspace_bytes.argtypes = [cp, i32]
+    lib.samkv_block_select.restype = ctypes.c_int
+    lib.samkv_block_select.argtypes = [vp, cp, i32, ctypes.POINTER(f32), i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_gather_q.restype = ctypes.c_int
     lib.samkv_gather_q.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, f32, vp, vp]
     lib.samkv_recompute_attn.restype = ctypes.c_int
@@ -199,6 +208,40 @@ def samkv_topk_select_v(scores: torch.Tensor, caches: Caches, p: Sequence[float]
 def samkv_gather_v(caches: Caches, idx: torch.Tensor, cu_k: Sequence[int], k_c: torch.Tensor, v_c: torch.Tensor) -> None:
     cu = (ctypes.c_int32 * (caches.n_ctx + 1))(*[int(x) for x in cu_k])
     _check(_lib.samkv_gather_v(ctypes.byref(caches.c), _ptr(idx), cu, _ptr(k_c), _ptr(v_c), _stream()), "samkv_gather_v")
+
+
+def samkv_block_scores(scores: torch.Tensor, caches: Caches, block: int, bscores: torch.Tensor) -> None:
+    """bscores [Hkv, sum ceil(L_i / block)] float32 <- mean token score of every block."""
+    assert scores.dtype == torch.float32 and bscores.dtype == torch.float32
+    assert tuple(bscores.shape) == (caches.n_kv_heads, sum(-(-n // block) for n in caches.lens))
+    _check(_lib.samkv_block_scores(_ptr(scores), ctypes.byref(caches.c), block, _ptr(bscores), _stream()),
+           "samkv_block_scores")
+
+
+def samkv_block_workspace_bytes(caches: Caches, block: int) -> int:
+    return int(_lib.samkv_block_workspace_bytes(ctypes.byref(caches.c), block))
+
+
+def samkv_block_select(bscores: torch.Tensor, caches: Caches, block: int, p: Sequence[float], n_init_blocks: int,
+                       n_local_blocks: int, idx: torch.Tensor, cu_k_dev: Optional[torch.Tensor],
+                       ws: torch.Tensor) -> List[int]:
+    """idx [Hkv, M] int32 <- token positions of the kept blocks; returns the host prefix sums of kept tokens."""
+    cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
+    pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    assert idx.dtype == torch.int32 and bscores.dtype == torch.float32
+    _check(_lib.samkv_block_select(_ptr(bscores), ctypes.byref(caches.c), block, pp, n_init_blocks, n_local_blocks,
+                                   _ptr(idx), _ptr(cu_k_dev), cu_k_host, _ptr(ws), ws.numel() * ws.element_size(),
+                                   _stream()), "samkv_block_select")
+    return list(cu_k_host)
+
+
+def samkv_gather_q_v(caches: Caches, q_cache: Sequence[torch.Tensor], idx: torch.Tensor, cu_k: Sequence[int],
+                     q_rec: torch.Tensor) -> None:
+    assert len(q_cache) == caches.n_ctx and idx.dtype == torch.int32
+    ptrs = (ctypes.c_void_p * caches.n_ctx)(*[t.data_ptr() for t in q_cache])
+    cu = (ctypes.c_int32 * (caches.n_ctx + 1))(*[int(x) for x in cu_k])
+    _check(_lib.samkv_gather_q_v(ctypes.byref(caches.c), ptrs, _ptr(idx), cu, _ptr(q_rec), _stream()),
+           "samkv_gather_q_v")
 
 
 def samkv_gather(caches: Caches, idx: torch.Tensor, ratio: float, k_c: torch.Tensor, v_c: torch.Tensor) -> None:

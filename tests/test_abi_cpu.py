@@ -107,6 +107,22 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_gather_q(ctypes.byref(ok), qp, None, 0.5, fake, None) == -1
     assert L.samkv_gather_q(ctypes.byref(ok), qp, fake, 0.0, fake, None) == -1
     assert L.samkv_gather_q(ctypes.byref(ok), (ctypes.c_void_p * 2)(0x1000, None), fake, 0.5, fake, None) == -1
+    # block-granular selection
+    pf = (ctypes.c_float * 2)(0.5, 0.5)
+    ragged = _caches(S, lens=(10, 8))
+    assert L.samkv_block_scores(None, ctypes.byref(ok), 4, fake, None) == -1
+    assert L.samkv_block_scores(fake, ctypes.byref(ok), 0, fake, None) == -1
+    assert L.samkv_block_scores(fake, ctypes.byref(ok), 5000, fake, None) == -1
+    assert L.samkv_block_workspace_bytes(ctypes.byref(ok), 0) == 0
+    assert L.samkv_block_workspace_bytes(ctypes.byref(ok), 4) >= 2 * 4 * 4
+    assert L.samkv_block_select(fake, ctypes.byref(ok), 4, None, 1, 1, fake, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_block_select(fake, ctypes.byref(ok), 4, pf, -1, 1, fake, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_block_select(fake, ctypes.byref(ok), 4, pf, 1, 1, fake, None, cu, None, 0, None) == -3
+    # a short last block that only some heads might keep: rejected (10 tokens in blocks of 4, no local block forced)
+    assert L.samkv_block_select(fake, ctypes.byref(ragged), 4, pf, 1, 0, fake, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_gather_q_v(ctypes.byref(ok), qp, fake, None, fake, None) == -1
+    assert L.samkv_gather_q_v(ctypes.byref(ok), qp, fake, (ctypes.c_int32 * 3)(0, 9, 12), fake, None) == -1   # 9 > len 8
+    assert L.samkv_gather_v(ctypes.byref(ok), fake, (ctypes.c_int32 * 3)(1, 2, 3), fake, fake, None) == -1
     # attention
     assert L.samkv_recompute_attn(None, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
     assert L.samkv_recompute_attn(fake, fake, fake, 0, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1

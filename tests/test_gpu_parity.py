@@ -309,3 +309,87 @@ def test_select_with_per_document_top_p_and_explicit_gather(S):
         S.samkv_gather_v(caches, idx, got_cu, k_c, v_c)
         k_ref, v_ref = O.gather(x.k, x.v, want, cu)
         assert np.array_equal(k_c.float().cpu().numpy(), k_ref) and np.array_equal(v_c.float().cpu().numpy(), v_ref)
+
+
+def test_block_level_scores_selection_and_gather(S):
+    """Sec. 3.2 at block granularity: block score = score of the mean key; initial / local blocks forced; the kept
+    blocks come back as token positions that gather_v and gather_q_v take.  Ragged last blocks, a document shorter
+    than one block, one made of forced blocks only, shares 0 and 1."""
+    import torch
+    lens = [700, 130, 64, 1500, 33, 4096 + 17]
+    x = synth.make_small(71, "bf16", lens, 8, 2, 128, 4, 8)
+    n = len(lens)
+    q_hat = O.personalized_query(x.q_tok, x.q_loc, n)
+    tok32 = [s.astype(np.float32) for s in O.score(q_hat, x.k)]
+    caches = H.upload_caches(x)
+    dev_scores = torch.from_numpy(np.concatenate(tok32, axis=1)).cuda()
+    q_cache = synth.make_q_cache(x.workload, 0, x.lens)
+    dev_q = [H.to_dev(q, "bf16") for q in q_cache]
+    for block, n_init, n_local, p in ((64, 1, 2, [0.25, 0.5, 0.3, 0.1, 1.0, 0.05]), (16, 2, 1, [0.0, 1.0, 0.5, 0.2, 0.4, 0.15]),
+                                      (64, 0, 1, [0.3, 0.0, 0.0, 0.2, 0.0, 0.1])):
+        nbs = [-(-L // block) for L in lens]
+        # (1) block scores: against the oracle's definition (mean key, fp64), and against the exact mean of the
+        #     same float32 token scores (only the kernel's own summation error is left)
+        b_ref = O.block_scores(q_hat, x.k, block)
+        bs = torch.full((2, sum(nbs)), float("nan"), dtype=torch.float32, device="cuda")
+        S.samkv_block_scores(dev_scores, caches, block, bs)
+        got = bs.cpu().numpy().astype(np.float64)
+        off = 0
+        for i, L in enumerate(lens):
+            smax = float(np.abs(tok32[i]).max())
+            g_i = got[:, off:off + nbs[i]]
+            assert np.abs(g_i - b_ref[i]).max() <= 2e-5 * smax + 1e-6, (block, i)
+            exact = np.stack([tok32[i][:, t * block:(t + 1) * block].astype(np.float64).mean(axis=1) for t in range(nbs[i])], axis=1)
+            assert np.abs(g_i - exact).max() <= block * 2.0 ** -24 * smax, (block, i)
+            off += nbs[i]
+        # (2) selection on the oracle's block scores rounded to float32: both sides decide on the same numbers
+        b32 = [b.astype(np.float32) for b in b_ref]
+        want, cu = O.block_select([b.astype(np.float64) for b in b32], lens, block, p, n_init, n_local)
+        m = int(cu[-1])
+        idx = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+        cu_dev = torch.zeros((n + 1,), dtype=torch.int32, device="cuda")
+        ws = torch.empty(S.samkv_block_workspace_bytes(caches, block), dtype=torch.uint8, device="cuda")
+        got_cu = S.samkv_block_select(torch.from_numpy(np.concatenate(b32, axis=1)).cuda(), caches, block, p, n_init,
+                                      n_local, idx, cu_dev, ws)
+        assert got_cu == cu.tolist() == cu_dev.cpu().tolist()
+        assert np.array_equal(idx.cpu().numpy(), want), (block, n_init, n_local)
+        # (3) the token positions feed the explicit-count gathers
+        k_c = torch.zeros((2, m, 128), dtype=torch.bfloat16, device="cuda")
+        v_c = torch.zeros_like(k_c)
+        S.samkv_gather_v(caches, idx, got_cu, k_c, v_c)
+        k_want, v_want = O.gather(x.k, x.v, want, cu)
+        assert np.array_equal(k_c.float().cpu().numpy(), k_want) and np.array_equal(v_c.float().cpu().numpy(), v_want)
+        q_rec = torch.zeros((8, m, 128), dtype=torch.bfloat16, device="cuda")
+        S.samkv_gather_q_v(caches, dev_q, idx, got_cu, q_rec)
+        assert np.array_equal(q_rec.float().cpu().numpy(), O.gather_q(q_cache, want, cu))
+        # (4) the whole chain on the device (token scores -> block scores -> selection): the kept block sets may
+        #     differ from the oracle's only at blocks whose score is within the tie margin of the threshold
+        idx2 = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+        assert S.samkv_block_select(bs, caches, block, p, n_init, n_local, idx2, None, ws) == cu.tolist()
+        got2 = idx2.cpu().numpy()
+        for g in range(2):
+            for i in range(n):
+                a, b = set(got2[g, cu[i]:cu[i + 1]].tolist()), set(want[g, cu[i]:cu[i + 1]].tolist())
+                if a == b:
+                    continue
+                kept_blocks = sorted({t // block for t in b})
+                free = [t for t in kept_blocks if n_init <= t < nbs[i] - n_local]
+                tau = min(b_ref[i][g, t] for t in free)
+                for t in {t // block for t in a ^ b}:
+                    assert abs(b_ref[i][g, t] - tau) <= H.TIE_MARGIN * max(1.0, abs(tau))
+
+
+def test_select_full_length_row_of_equal_scores(S):
+    """A maximum-length row whose scores are all equal: ties go to the lower positions, and a full budget keeps all
+    65536 of them (the counts of the ordered compaction reach 2^16)."""
+    import torch
+    L = 65536
+    k = torch.zeros((1, L, 64), dtype=torch.float32, device="cuda")
+    caches = S.Caches([k], None, 1)
+    sc = np.full((1, L), 0.25, np.float32)
+    dev = torch.from_numpy(sc).cuda()
+    for ratio, n_sink, n_local in ((1.0, 0, 0), (0.5, 0, 0), (0.25, 4, 100)):
+        want, cu = O.select([sc.astype(np.float64)], ratio, n_sink, n_local)
+        idx = torch.full((1, int(cu[-1])), -1, dtype=torch.int32, device="cuda")
+        assert S.samkv_topk_select(dev, caches, ratio, n_sink, n_local, idx, None) == cu.tolist()
+        assert np.array_equal(idx.cpu().numpy(), want)

@@ -532,3 +532,43 @@ def test_kept_count_mid_and_select_v():
         best = np.argsort(-scores[0][g, 2:27], kind="stable")[:5] + 2
         assert sorted(mid) == sorted(best.tolist())
         assert idx[g, 10:15].tolist() == [0, 1, 9, 10, 11]             # a document with P = 0 keeps only the forced ones
+
+
+# ------------------------------------------------------------------ block-level retrieval (Sec. 3.2)
+def test_block_scores_hand_values_and_linearity():
+    # one head, d = 1, keys 1..5 in blocks of 2 -> representatives 1.5, 3.5, 5; Q^ = 2 -> scores 3, 7, 10
+    k = [np.arange(1.0, 6.0).reshape(1, 5, 1)]
+    assert np.array_equal(O.block_scores(np.full((1, 1, 1), 2.0), k, 2)[0], [[3.0, 7.0, 10.0]])
+    # the inner product is linear: the score of the mean key is the mean of the token scores (ragged last block,
+    # grouped heads); O.score on the tokens is an independent path to the same number
+    r = rng(90)
+    lens, hq, hkv, d, block = (37, 64, 5), 4, 2, 8, 16
+    ks = [r.standard_normal((hkv, L, d)) for L in lens]
+    q_hat = r.standard_normal((3, hq, d))
+    tok = O.score(q_hat, ks)
+    for i, b in enumerate(O.block_scores(q_hat, ks, block)):
+        assert b.shape == (hkv, -(-lens[i] // block))
+        for n in range(b.shape[1]):
+            want = tok[i][:, n * block:(n + 1) * block].mean(axis=1)
+            assert np.allclose(b[:, n], want, rtol=1e-12, atol=1e-12)
+
+
+def test_block_select_hand_values_and_token_granularity_special_case():
+    # 10 tokens in blocks of 3: blocks 0..3, the last holds token 9 only.  First and last block forced, half of the
+    # two middle blocks -> one more, the better of blocks 1 (score 1) and 2 (score 5).
+    b = [np.array([[0.0, 1.0, 5.0, -3.0], [9.0, 2.0, 1.0, 9.0]])]
+    idx, cu_k = O.block_select(b, [10], 3, [0.5], 1, 1)
+    assert cu_k.tolist() == [0, 7]
+    assert idx.tolist() == [[0, 1, 2, 6, 7, 8, 9], [0, 1, 2, 3, 4, 5, 9]]
+    # p = 0 keeps only the forced blocks, p = 1 everything
+    assert O.block_select(b, [10], 3, [0.0], 1, 1)[0].tolist() == [[0, 1, 2, 9]] * 2
+    assert O.block_select(b, [10], 3, [1.0], 1, 1)[0].tolist() == [list(range(10))] * 2
+    # blocks of one token are the token-level selection
+    r = rng(91)
+    sc = [r.standard_normal((3, L)) for L in (17, 40)]
+    a = O.block_select(sc, [17, 40], 1, [0.3, 0.6], 2, 3)
+    w = O.select_v(sc, [0.3, 0.6], 2, 3)
+    assert np.array_equal(a[0], w[0]) and np.array_equal(a[1], w[1])
+    # heads that would keep different token counts are refused (short last block neither forced nor dropped by all)
+    with pytest.raises(AssertionError):
+        O.block_select([np.array([[0.0, 1.0, 5.0, -3.0], [9.0, 2.0, 1.0, 9.0]])], [10], 3, [0.5], 1, 0)
