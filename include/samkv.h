@@ -163,6 +163,37 @@ int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t
                        int32_t n_init_blocks, int32_t n_local_blocks, int32_t* idx, int32_t* cu_k_dev,
                        int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream);
 
+/* Sec. 3.2, second filter across documents, on top of samkv_block_select.  Per KV head: the candidates are the
+ * middle blocks that the per-document selection retrieved; each document's candidate scores are normalised, the
+ * candidates of all documents are compared, and keep = ceil(candidates / n_ctx) of them survive (the paper: the
+ * total block count divided by the number of documents).  Forced initial / local blocks always survive.
+ * READING, not fixed by the paper (it names a normalisation but does not define it): min-max per document and KV
+ * head over its candidates, (s - min) / (max - min) in float32, 1 when max == min; equal normalised scores go to
+ * the earlier document, then the lower block.
+ * The documents' shares now differ from head to head, so the result is one row of GLOBAL token positions per
+ * head (position in the concatenation of all documents, cu_len[i] + t), ascending:
+ *   gidx   [Hkv][M] int32 written, M = samkv_block_filter_count(...) (same for every head)
+ *   ws     samkv_block_workspace_bytes(caches, block) bytes, 256-byte aligned
+ * Every candidate must be a full block: a document with a short last block needs n_local_blocks >= 1
+ * (SAMKV_EINVAL otherwise); more than SAMKV_MAX_LEN retrieved blocks in total is SAMKV_EUNSUPPORTED. */
+int samkv_block_select_filter(const float* bscores, const samkv_caches* caches, int32_t block, const float* p,
+                              int32_t n_init_blocks, int32_t n_local_blocks, int32_t* gidx, void* ws,
+                              size_t ws_bytes, void* stream);
+
+/* Tokens per KV head that samkv_block_select_filter keeps (host arithmetic); 0 for invalid arguments. */
+int32_t samkv_block_filter_count(const samkv_caches* caches, int32_t block, const float* p,
+                                 int32_t n_init_blocks, int32_t n_local_blocks);
+
+/* Compaction by global token positions: K_c[g][m][:] = K_i[g][gidx[g][m] - cu_len[i]][:] with i the document that
+ * holds the position, same for V; bit-exact copies.  gidx [Hkv][m_total] device (out-of-range values are clamped);
+ * k_c, v_c [Hkv][m_total][d] written. */
+int samkv_gather_g(const samkv_caches* caches, const int32_t* gidx, int32_t m_total, void* k_c, void* v_c,
+                   void* stream);
+
+/* The same for the stored Q caches (as samkv_gather_q): q_rec[h][m][:] = Q_i[h][gidx[h / G][m] - cu_len[i]][:]. */
+int samkv_gather_q_g(const samkv_caches* caches, const void* const* q_cache, const int32_t* gidx, int32_t m_total,
+                     void* q_rec, void* stream);
+
 /* samkv_gather with the kept counts given explicitly: cu_k_host is host [n_ctx + 1], the exclusive prefix
  * sum that the selection returned. */
 int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t* cu_k_host, void* k_c,

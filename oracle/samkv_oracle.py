@@ -16,6 +16,8 @@ the order and notation of the paper:
   kept_count           budget ratio -> number of kept tokens per document and head
   select_row / select  Sec. 3.2: keep the top-scoring share of each document (initial/local kept first)
   block_scores / block_select   Sec. 3.2 block-level retrieval: mean-key block representatives, forced blocks
+  block_filter         Sec. 3.2 second filter across documents (normalisation is a reading: parity unpinned)
+  gather_global        compaction by positions in the concatenation of all documents
   gather, gather_q     Sec. 3.2: concatenate the kept K/V (and stored Q) of all documents in their original order
   kv_update            Sec. 3.3, Eq. 4: overwrite or cosine-weighted fusion of recomputed K/V rows
   attention            Sec. 3.3 recomputation (causal over the compacted cache) and the final
@@ -30,7 +32,9 @@ selection go to the lower position; with one document the bias term vanishes;
 a cosine with a zero-norm argument counts as 0.
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
-(closed forms, hand-worked cases, brute force, library routines).  The quality
+(closed forms, hand-worked cases, brute force, library routines), except block_filter:
+parity unpinned (the paper does not define its normalisation; the mechanics around the
+reading are pinned, the reading itself cannot be).  The quality
 of the whole pipeline (the paper's F1 tables) needs datasets and weights and is
 parity unpinned.
 """
@@ -238,6 +242,65 @@ def block_select(bscores: Sequence[np.ndarray], lens: Sequence[int], block: int,
         cu_k.append(cu_k[-1] + n_tok)
     idx = np.stack([np.concatenate(r) for r in rows]).astype(np.int32)
     return idx, np.asarray(cu_k, np.int32)
+
+
+def block_filter(bscores: Sequence[np.ndarray], lens: Sequence[int], block: int, p: Sequence[float],
+                 n_init_blocks: int = 1, n_local_blocks: int = 2) -> np.ndarray:
+    """Second filter of Sec. 3.2 on top of block_select.  PARITY UNPINNED as far as the normalisation goes: the
+    paper says the retrieved blocks' inner products are normalised across documents before they are compared, and
+    that as many blocks survive as the total block count divided by the number of documents, but gives no formula.
+    Reading implemented (the library documents the same one):
+      * candidates: per KV head, the middle (non-forced) blocks that the per-document Top-P_i selection retrieved;
+      * normalisation: min-max per document and head over its candidates, (s - min) / (max - min), evaluated in
+        float32 (the decision is taken in the precision the kernel works in), 1 when max == min;
+      * survivors: the ceil(C / N) candidates with the largest normalised score, C = number of candidates (the
+        same for every head), ties to the earlier document and then the lower block;
+      * forced blocks survive unconditionally.
+    Returns the GLOBAL token positions (offset of the document in the concatenation + position) of the surviving
+    blocks, ascending, one row per KV head: [Hkv, M]."""
+    f32 = np.float32
+    hkv, n_ctx = bscores[0].shape[0], len(lens)
+    cu_len = np.concatenate([[0], np.cumsum(lens)])
+    rows = []
+    for g in range(hkv):
+        forced_blocks, cands = [], []          # (document, block) and (normalised score, document, block)
+        for i, (b, L) in enumerate(zip(bscores, lens)):
+            nb = b.shape[1]
+            kb = kept_count_mid(nb, p[i], n_init_blocks, n_local_blocks)
+            if kb == 0:
+                continue
+            ni = min(n_init_blocks, nb)
+            nl = min(n_local_blocks, nb - ni)
+            kept = select_row(np.asarray(b[g], F64), kb, ni, nl)
+            mid = [int(n) for n in kept if ni <= n < nb - nl]
+            forced_blocks += [(i, int(n)) for n in kept if not (ni <= n < nb - nl)]
+            if mid:
+                sc = np.asarray([b[g, n] for n in mid]).astype(f32)
+                mn, mx = sc.min(), sc.max()
+                rng_ = f32(mx - mn)
+                for n, s in zip(mid, sc):
+                    cands.append((float(f32(s - mn) / rng_) if rng_ > 0 else 1.0, i, n))
+        keep = -(-len(cands) // n_ctx)
+        best = sorted(cands, key=lambda c: (-c[0], c[1], c[2]))[:keep]
+        blocks = sorted(forced_blocks + [(i, n) for _, i, n in best])
+        toks = [np.arange(cu_len[i] + n * block, cu_len[i] + min(lens[i], (n + 1) * block)) for i, n in blocks]
+        rows.append(np.concatenate(toks).astype(np.int32))
+    assert len({r.shape[0] for r in rows}) == 1, "heads keep different numbers of tokens"
+    return np.stack(rows)
+
+
+def gather_global(x: Sequence[np.ndarray], gidx: np.ndarray, group: int = 1) -> np.ndarray:
+    """Compaction by global token positions: out[h, m, :] = x_i[h, gidx[h // group, m] - cu_len[i], :] with i the
+    document that holds the position.  x[i] [H, L_i, d]; returns [H, M, d]."""
+    lens = [a.shape[1] for a in x]
+    cu_len = np.concatenate([[0], np.cumsum(lens)])
+    H, _, d = x[0].shape
+    out = np.empty((H, gidx.shape[1], d), x[0].dtype)
+    for h in range(H):
+        for m, gp in enumerate(gidx[h // group]):
+            i = int(np.searchsorted(cu_len, gp, side="right")) - 1
+            out[h, m] = x[i][h, gp - cu_len[i]]
+    return out
 
 
 # --------------------------------------------------------------------------- compaction

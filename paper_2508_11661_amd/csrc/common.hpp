@@ -56,6 +56,14 @@ hipError_t launch_block_scores(const float* scores, const IntTable& cu_len, cons
 hipError_t launch_expand_blocks(const int32_t* bidx, const IntTable& cu_len, const IntTable& cu_kb, const IntTable& cu_k,
                                 int n_ctx, int hkv, int block, int32_t* idx, int32_t* cu_k_dev, hipStream_t s);
 
+hipError_t launch_gather_g(int row_bytes, const PtrTable& a, const PtrTable* b, const IntTable& cu_len, int n_ctx, int heads,
+                           int group, int m_total, const int32_t* gidx, void* a_out, void* b_out, hipStream_t s);
+hipError_t launch_normalize(const float* bscores, const int32_t* bidx, const IntTable& cu_blk, const IntTable& cu_kb,
+                            int n_ctx, int hkv, int n_init, int n_local, float* cand, hipStream_t s);
+hipError_t launch_filter_expand(const int32_t* sel, const int32_t* bidx, const IntTable& cu_len, const IntTable& cu_kb,
+                                int n_ctx, int hkv, int n_sel, int m_total, int block, int32_t* start, int32_t* tok_off,
+                                int32_t* gidx, hipStream_t s);
+
 struct GatherLaunch {
   int n_ctx, hkv, row_bytes, m_total, max_k;
   const int32_t* idx;

@@ -279,11 +279,63 @@ static int block_table(const samkv_caches* caches, const Shape& s, int block, In
   return SAMKV_OK;
 }
 
+// Counts of the per-document block selection, and of the cross-document filter on top of it.
+struct BlockPlan {
+  IntTable cu_blk, cu_kb, cu_k;  // blocks, kept blocks, kept tokens of the per-document selection (prefix sums)
+  int max_nb;
+  int forced_blocks, forced_tokens, cand, keep;  // filter: candidates = kept middle blocks, keep = ceil(cand / n_ctx)
+  bool any_short_unforced;                       // some document's short last block is not a forced block
+};
+
+static int block_plan(const samkv_caches* caches, const Shape& s, int block, const float* p, int n_init, int n_local,
+                      BlockPlan* bp) {
+  if (p == nullptr || n_init < 0 || n_local < 0) return SAMKV_EINVAL;
+  int rc = block_table(caches, s, block, &bp->cu_blk);
+  if (rc != SAMKV_OK) return rc;
+  bp->cu_kb.v[0] = 0;
+  bp->cu_k.v[0] = 0;
+  bp->max_nb = 0;
+  bp->forced_blocks = bp->forced_tokens = bp->cand = 0;
+  bp->any_short_unforced = false;
+  for (int i = 0; i < s.n_ctx; ++i) {
+    const int L = caches->len[i], nb = bp->cu_blk.v[i + 1] - bp->cu_blk.v[i];
+    const int kb = kept_count_mid(nb, p[i], n_init, n_local);
+    if (kb < 0) return SAMKV_EINVAL;
+    const bool short_last = L % block != 0;
+    const long long forced_ll = (long long)n_init + n_local;
+    const int forced = forced_ll >= nb ? nb : (int)forced_ll;
+    // a short last block must be kept by every head or by none: it is kept whenever local blocks are forced
+    if (short_last && n_local == 0 && kb != 0 && kb != nb) return SAMKV_EINVAL;
+    if (short_last && n_local == 0 && forced < nb) bp->any_short_unforced = true;
+    const bool last_kept = kb == nb || (n_local > 0 && kb > 0);
+    const int tokens = kb * block - ((last_kept && short_last) ? (block - L % block) : 0);
+    bp->cu_kb.v[i + 1] = bp->cu_kb.v[i] + kb;
+    bp->cu_k.v[i + 1] = bp->cu_k.v[i] + tokens;
+    if (nb > bp->max_nb) bp->max_nb = nb;
+    bp->forced_blocks += forced;
+    bp->forced_tokens += forced == nb ? L : n_init * block + (L - (nb - n_local) * block);
+    bp->cand += kb - forced;
+  }
+  bp->keep = (bp->cand + s.n_ctx - 1) / s.n_ctx;
+  return bp->cu_k.v[s.n_ctx] >= 1 ? SAMKV_OK : SAMKV_EINVAL;
+}
+
+static hipError_t block_select_launch(const float* bscores, const Shape& s, const BlockPlan& bp, int n_init, int n_local,
+                                      int32_t* bidx, hipStream_t st) {
+  SelectLaunch a;
+  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.max_len = bp.max_nb; a.total_len = bp.cu_blk.v[s.n_ctx];
+  a.m_total = bp.cu_kb.v[s.n_ctx]; a.n_sink = n_init; a.n_local = n_local;
+  a.scores = bscores; a.idx = bidx; a.cu_k_dev = nullptr;
+  return launch_select(a, bp.cu_blk, bp.cu_kb, st);
+}
+
 size_t samkv_block_workspace_bytes(const samkv_caches* caches, int32_t block) {
   Shape s;
   IntTable cu_blk;
   if (check_caches(caches, false, false, &s) != SAMKV_OK || block_table(caches, s, block, &cu_blk) != SAMKV_OK) return 0;
-  return align_up((size_t)s.hkv * cu_blk.v[s.n_ctx] * 4) + kAlign;
+  // kept block ids; for the filter also the candidates' normalised scores, the kept candidates, their first token
+  // positions and output offsets: five arrays of at most [Hkv][sum of blocks] 4-byte entries
+  return 5 * align_up((size_t)s.hkv * cu_blk.v[s.n_ctx] * 4) + kAlign;
 }
 
 int samkv_block_scores(const float* scores, const samkv_caches* caches, int32_t block, float* bscores, void* stream) {
@@ -304,39 +356,101 @@ int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t
   Shape s;
   int rc = check_caches(caches, false, false, &s);
   if (rc != SAMKV_OK) return rc;
-  if (bscores == nullptr || idx == nullptr || p == nullptr || n_init_blocks < 0 || n_local_blocks < 0) return SAMKV_EINVAL;
-  IntTable cu_blk, cu_kb, cu_k;
-  rc = block_table(caches, s, block, &cu_blk);
+  if (bscores == nullptr || idx == nullptr) return SAMKV_EINVAL;
+  BlockPlan bp;
+  rc = block_plan(caches, s, block, p, n_init_blocks, n_local_blocks, &bp);
   if (rc != SAMKV_OK) return rc;
-  cu_kb.v[0] = 0;
-  cu_k.v[0] = 0;
-  int max_nb = 0;
-  for (int i = 0; i < s.n_ctx; ++i) {
-    const int L = caches->len[i], nb = cu_blk.v[i + 1] - cu_blk.v[i];
-    const int kb = kept_count_mid(nb, p[i], n_init_blocks, n_local_blocks);
-    if (kb < 0) return SAMKV_EINVAL;
-    const bool short_last = L % block != 0;
-    // a short last block must be kept by every head or by none: it is kept whenever local blocks are forced
-    if (short_last && n_local_blocks == 0 && kb != 0 && kb != nb) return SAMKV_EINVAL;
-    const bool last_kept = kb == nb || (n_local_blocks > 0 && kb > 0);
-    const int tokens = kb * block - ((last_kept && short_last) ? (block - L % block) : 0);
-    cu_kb.v[i + 1] = cu_kb.v[i] + kb;
-    cu_k.v[i + 1] = cu_k.v[i] + tokens;
-    if (nb > max_nb) max_nb = nb;
-  }
-  if (cu_k.v[s.n_ctx] < 1) return SAMKV_EINVAL;
-  const size_t need = align_up((size_t)s.hkv * cu_blk.v[s.n_ctx] * 4);
+  const size_t need = align_up((size_t)s.hkv * bp.cu_blk.v[s.n_ctx] * 4);
   if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return SAMKV_EWORKSPACE;
-  if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
+  if (cu_k_host != nullptr) memcpy(cu_k_host, bp.cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
   int32_t* bidx = static_cast<int32_t*>(ws);
-  SelectLaunch a;
-  a.n_ctx = s.n_ctx; a.hkv = s.hkv; a.max_len = max_nb; a.total_len = cu_blk.v[s.n_ctx];
-  a.m_total = cu_kb.v[s.n_ctx]; a.n_sink = n_init_blocks; a.n_local = n_local_blocks;
-  a.scores = bscores; a.idx = bidx; a.cu_k_dev = nullptr;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e = launch_select(a, cu_blk, cu_kb, st);
-  if (e == hipSuccess) e = launch_expand_blocks(bidx, s.cu_len, cu_kb, cu_k, s.n_ctx, s.hkv, block, idx, cu_k_dev, st);
+  hipError_t e = block_select_launch(bscores, s, bp, n_init_blocks, n_local_blocks, bidx, st);
+  if (e == hipSuccess)
+    e = launch_expand_blocks(bidx, s.cu_len, bp.cu_kb, bp.cu_k, s.n_ctx, s.hkv, block, idx, cu_k_dev, st);
   return dev(e);
+}
+
+int32_t samkv_block_filter_count(const samkv_caches* caches, int32_t block, const float* p, int32_t n_init_blocks,
+                                 int32_t n_local_blocks) {
+  Shape s;
+  BlockPlan bp;
+  if (check_caches(caches, false, false, &s) != SAMKV_OK ||
+      block_plan(caches, s, block, p, n_init_blocks, n_local_blocks, &bp) != SAMKV_OK || bp.any_short_unforced)
+    return 0;
+  return bp.forced_tokens + bp.keep * block;
+}
+
+int samkv_block_select_filter(const float* bscores, const samkv_caches* caches, int32_t block, const float* p,
+                              int32_t n_init_blocks, int32_t n_local_blocks, int32_t* gidx, void* ws, size_t ws_bytes,
+                              void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (bscores == nullptr || gidx == nullptr) return SAMKV_EINVAL;
+  BlockPlan bp;
+  rc = block_plan(caches, s, block, p, n_init_blocks, n_local_blocks, &bp);
+  if (rc != SAMKV_OK) return rc;
+  if (bp.any_short_unforced) return SAMKV_EINVAL;  // every candidate must be a full block
+  const int total_kb = bp.cu_kb.v[s.n_ctx];
+  if (total_kb > SAMKV_MAX_LEN) return SAMKV_EUNSUPPORTED;  // the candidates of one head form one selection row
+  const int n_sel = bp.forced_blocks + bp.keep;
+  const int m_total = bp.forced_tokens + bp.keep * block;
+  if (n_sel < 1 || m_total < 1) return SAMKV_EINVAL;
+  const size_t slab = align_up((size_t)s.hkv * bp.cu_blk.v[s.n_ctx] * 4);
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < 5 * slab) return SAMKV_EWORKSPACE;
+  char* w = static_cast<char*>(ws);
+  int32_t* bidx = reinterpret_cast<int32_t*>(w);
+  float* cand = reinterpret_cast<float*>(w + slab);
+  int32_t* sel = reinterpret_cast<int32_t*>(w + 2 * slab);
+  int32_t* start = reinterpret_cast<int32_t*>(w + 3 * slab);
+  int32_t* tok_off = reinterpret_cast<int32_t*>(w + 4 * slab);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = block_select_launch(bscores, s, bp, n_init_blocks, n_local_blocks, bidx, st);
+  if (e == hipSuccess)
+    e = launch_normalize(bscores, bidx, bp.cu_blk, bp.cu_kb, s.n_ctx, s.hkv, n_init_blocks, n_local_blocks, cand, st);
+  if (e == hipSuccess) {
+    // all candidates of a KV head as one row; the forced ones carry +inf and are within the budget by construction
+    IntTable row, kept;
+    row.v[0] = 0; row.v[1] = total_kb;
+    kept.v[0] = 0; kept.v[1] = n_sel;
+    SelectLaunch a;
+    a.n_ctx = 1; a.hkv = s.hkv; a.max_len = total_kb; a.total_len = total_kb; a.m_total = n_sel;
+    a.n_sink = 0; a.n_local = 0; a.scores = cand; a.idx = sel; a.cu_k_dev = nullptr;
+    e = launch_select(a, row, kept, st);
+  }
+  if (e == hipSuccess)
+    e = launch_filter_expand(sel, bidx, s.cu_len, bp.cu_kb, s.n_ctx, s.hkv, n_sel, m_total, block, start, tok_off, gidx, st);
+  return dev(e);
+}
+
+int samkv_gather_g(const samkv_caches* caches, const int32_t* gidx, int32_t m_total, void* k_c, void* v_c, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, true, true, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (gidx == nullptr || k_c == nullptr || v_c == nullptr || m_total < 1) return SAMKV_EINVAL;
+  PtrTable kt, vt;
+  memset(&kt, 0, sizeof(kt));
+  memset(&vt, 0, sizeof(vt));
+  for (int i = 0; i < s.n_ctx; ++i) { kt.p[i] = caches->k[i]; vt.p[i] = caches->v[i]; }
+  return dev(launch_gather_g(s.d * (s.dtype == SAMKV_BF16 ? 2 : 4), kt, &vt, s.cu_len, s.n_ctx, s.hkv, 1, m_total, gidx,
+                             k_c, v_c, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_gather_q_g(const samkv_caches* caches, const void* const* q_cache, const int32_t* gidx, int32_t m_total,
+                     void* q_rec, void* stream) {
+  Shape s;
+  int rc = check_caches(caches, false, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_cache == nullptr || gidx == nullptr || q_rec == nullptr || m_total < 1) return SAMKV_EINVAL;
+  PtrTable qt;
+  memset(&qt, 0, sizeof(qt));
+  for (int i = 0; i < s.n_ctx; ++i) {
+    if (q_cache[i] == nullptr) return SAMKV_EINVAL;
+    qt.p[i] = q_cache[i];
+  }
+  return dev(launch_gather_g(s.d * (s.dtype == SAMKV_BF16 ? 2 : 4), qt, nullptr, s.cu_len, s.n_ctx, s.hq, s.hq / s.hkv,
+                             m_total, gidx, q_rec, nullptr, static_cast<hipStream_t>(stream)));
 }
 
 static int gather_common(const samkv_caches* caches, const Shape& s, const IntTable& cu_k, const int32_t* idx,

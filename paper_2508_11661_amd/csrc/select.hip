@@ -112,49 +112,6 @@ __global__ __launch_bounds__(NT) void k_select(const float* scores, IntTable cu_
   }
 }
 
-// Block score = mean of the token scores of the block.  The paper represents a block by the mean of its
-// keys (Sec. 3.2); the inner product is linear, so that is the mean of the inner products already computed.
-// 16 lanes per block, fixed summation order inside a lane and a DPP tree across lanes.
-template <int CTRL>
-__device__ __forceinline__ float dpp_mv(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-__global__ __launch_bounds__(256) void k_block_scores(const float* scores, IntTable cu_len, IntTable cu_blk, int total_len,
-                                                      int total_blk, int block, float* bscores) {
-  const int i = blockIdx.y, g = blockIdx.z;
-  const int L = cu_len.v[i + 1] - cu_len.v[i];
-  const int nb = cu_blk.v[i + 1] - cu_blk.v[i];
-  const int b = blockIdx.x * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
-  if (b >= nb) return;   // whole 16-lane groups leave together; the DPP steps below stay inside a group
-  const float* row = scores + (size_t)g * total_len + cu_len.v[i];
-  const int t0 = b * block, t1 = min(L, t0 + block);
-  float acc = 0.f;
-  for (int t = t0 + sub; t < t1; t += 16) acc += row[t];
-  acc += dpp_mv<0xB1>(acc);
-  acc += dpp_mv<0x4E>(acc);
-  acc += dpp_mv<0x141>(acc);
-  acc += dpp_mv<0x140>(acc);
-  if (sub == 0) bscores[(size_t)g * total_blk + cu_blk.v[i] + b] = acc / (float)(t1 - t0);
-}
-
-// Kept blocks (ascending block ids, per document and KV head) -> kept token positions.  Only a document's last
-// block can be short, and it is last among the kept ones, so the t-th kept block starts at token offset t * block.
-__global__ __launch_bounds__(256) void k_expand_blocks(const int32_t* bidx, IntTable cu_len, IntTable cu_kb, IntTable cu_k,
-                                                       int total_kb, int m_total, int n_ctx, int block, int32_t* idx,
-                                                       int32_t* cu_k_dev) {
-  const int i = blockIdx.y, g = blockIdx.z;
-  if (cu_k_dev != nullptr && i == 0 && g == 0 && blockIdx.x == 0)
-    for (int n = threadIdx.x; n <= n_ctx; n += 256) cu_k_dev[n] = cu_k.v[n];
-  const int L = cu_len.v[i + 1] - cu_len.v[i];
-  const int k_i = cu_k.v[i + 1] - cu_k.v[i];
-  const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= k_i) return;
-  const int t = r / block, e = r - t * block;
-  const int b = bidx[(size_t)g * total_kb + cu_kb.v[i] + t];
-  const int pos = b * block + e;
-  idx[(size_t)g * m_total + cu_k.v[i] + r] = pos < L ? pos : L - 1;
-}
-
 template <int E, int NT>
 hipError_t run(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s) {
   hipLaunchKernelGGL((k_select<E, NT>), dim3(a.n_ctx, a.hkv), dim3(NT), 0, s, a.scores, cu_len, cu_k, a.total_len,
@@ -170,24 +127,6 @@ hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const In
   if (a.max_len <= 4096) return run<16, 256>(a, cu_len, cu_k, s);
   if (a.max_len <= 16384) return run<16, 1024>(a, cu_len, cu_k, s);
   return run<64, 1024>(a, cu_len, cu_k, s);
-}
-
-hipError_t launch_block_scores(const float* scores, const IntTable& cu_len, const IntTable& cu_blk, int n_ctx, int hkv,
-                               int total_len, int block, float* bscores, hipStream_t s) {
-  int max_nb = 0;
-  for (int i = 0; i < n_ctx; ++i) max_nb = cu_blk.v[i + 1] - cu_blk.v[i] > max_nb ? cu_blk.v[i + 1] - cu_blk.v[i] : max_nb;
-  hipLaunchKernelGGL(k_block_scores, dim3((max_nb + 15) / 16, n_ctx, hkv), dim3(256), 0, s, scores, cu_len, cu_blk,
-                     total_len, cu_blk.v[n_ctx], block, bscores);
-  return hipGetLastError();
-}
-
-hipError_t launch_expand_blocks(const int32_t* bidx, const IntTable& cu_len, const IntTable& cu_kb, const IntTable& cu_k,
-                                int n_ctx, int hkv, int block, int32_t* idx, int32_t* cu_k_dev, hipStream_t s) {
-  int max_k = 0;
-  for (int i = 0; i < n_ctx; ++i) max_k = cu_k.v[i + 1] - cu_k.v[i] > max_k ? cu_k.v[i + 1] - cu_k.v[i] : max_k;
-  hipLaunchKernelGGL(k_expand_blocks, dim3((max_k + 255) / 256 > 0 ? (max_k + 255) / 256 : 1, n_ctx, hkv), dim3(256), 0, s,
-                     bidx, cu_len, cu_kb, cu_k, cu_kb.v[n_ctx], cu_k.v[n_ctx], n_ctx, block, idx, cu_k_dev);
-  return hipGetLastError();
 }
 
 }  // namespace samkv

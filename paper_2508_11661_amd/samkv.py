@@ -20,6 +20,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
            "samkv_score", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
+           "samkv_block_select_filter", "samkv_block_filter_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
            "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
@@ -68,6 +69,14 @@ def _load() -> ctypes.CDLL:
     lib.samkv_block_workspace_bytes.argtypes = [cp, i32]
     lib.samkv_block_select.restype = ctypes.c_int
     lib.samkv_block_select.argtypes = [vp, cp, i32, ctypes.POINTER(f32), i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.samkv_block_select_filter.restype = ctypes.c_int
+    lib.samkv_block_select_filter.argtypes = [vp, cp, i32, ctypes.POINTER(f32), i32, i32, vp, vp, sz, vp]
+    lib.samkv_block_filter_count.restype = i32
+    lib.samkv_block_filter_count.argtypes = [cp, i32, ctypes.POINTER(f32), i32, i32]
+    lib.samkv_gather_g.restype = ctypes.c_int
+    lib.samkv_gather_g.argtypes = [cp, vp, i32, vp, vp, vp]
+    lib.samkv_gather_q_g.restype = ctypes.c_int
+    lib.samkv_gather_q_g.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, i32, vp, vp]
     lib.samkv_gather_q.restype = ctypes.c_int
     lib.samkv_gather_q.argtypes = [cp, ctypes.POINTER(ctypes.c_void_p), vp, f32, vp, vp]
     lib.samkv_recompute_attn.restype = ctypes.c_int
@@ -233,6 +242,37 @@ def samkv_block_select(bscores: torch.Tensor, caches: Caches, block: int, p: Seq
                                    _ptr(idx), _ptr(cu_k_dev), cu_k_host, _ptr(ws), ws.numel() * ws.element_size(),
                                    _stream()), "samkv_block_select")
     return list(cu_k_host)
+
+
+def samkv_block_filter_count(caches: Caches, block: int, p: Sequence[float], n_init_blocks: int,
+                             n_local_blocks: int) -> int:
+    pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    return int(_lib.samkv_block_filter_count(ctypes.byref(caches.c), block, pp, n_init_blocks, n_local_blocks))
+
+
+def samkv_block_select_filter(bscores: torch.Tensor, caches: Caches, block: int, p: Sequence[float], n_init_blocks: int,
+                              n_local_blocks: int, gidx: torch.Tensor, ws: torch.Tensor) -> None:
+    """gidx [Hkv, M] int32 <- global token positions kept after the cross-document filter."""
+    pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    assert gidx.dtype == torch.int32 and bscores.dtype == torch.float32
+    assert gidx.shape[1] == samkv_block_filter_count(caches, block, p, n_init_blocks, n_local_blocks)
+    _check(_lib.samkv_block_select_filter(_ptr(bscores), ctypes.byref(caches.c), block, pp, n_init_blocks,
+                                          n_local_blocks, _ptr(gidx), _ptr(ws), ws.numel() * ws.element_size(),
+                                          _stream()), "samkv_block_select_filter")
+
+
+def samkv_gather_g(caches: Caches, gidx: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor) -> None:
+    assert gidx.dtype == torch.int32 and tuple(k_c.shape) == (caches.n_kv_heads, gidx.shape[1], caches.head_dim)
+    _check(_lib.samkv_gather_g(ctypes.byref(caches.c), _ptr(gidx), int(gidx.shape[1]), _ptr(k_c), _ptr(v_c), _stream()),
+           "samkv_gather_g")
+
+
+def samkv_gather_q_g(caches: Caches, q_cache: Sequence[torch.Tensor], gidx: torch.Tensor, q_rec: torch.Tensor) -> None:
+    assert len(q_cache) == caches.n_ctx and gidx.dtype == torch.int32
+    assert tuple(q_rec.shape) == (caches.n_q_heads, gidx.shape[1], caches.head_dim)
+    ptrs = (ctypes.c_void_p * caches.n_ctx)(*[t.data_ptr() for t in q_cache])
+    _check(_lib.samkv_gather_q_g(ctypes.byref(caches.c), ptrs, _ptr(gidx), int(gidx.shape[1]), _ptr(q_rec), _stream()),
+           "samkv_gather_q_g")
 
 
 def samkv_gather_q_v(caches: Caches, q_cache: Sequence[torch.Tensor], idx: torch.Tensor, cu_k: Sequence[int],

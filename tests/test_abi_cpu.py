@@ -58,6 +58,24 @@ def test_top_p_and_mid_counts_match_oracle(S):
         assert S.samkv_kept_count_mid(L, p, a, b) == O.kept_count_mid(L, p, a, b), (L, p, a, b)
 
 
+def test_block_filter_count_matches_oracle(S):
+    """Host arithmetic of the cross-document filter: tokens kept per head = what the oracle's rows hold."""
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        n = int(rng.integers(1, 6))
+        block = int(rng.choice([1, 4, 16, 64]))
+        lens = [int(rng.integers(1, 40 * block)) for _ in range(n)]
+        p = [float(x) for x in rng.choice([0.0, 0.1, 0.33, 0.5, 1.0], n)]
+        n_init, n_local = int(rng.integers(0, 3)), int(rng.integers(1, 3))
+        bs = [rng.standard_normal((1, -(-L // block))) for L in lens]
+        want = O.block_filter(bs, lens, block, p, n_init, n_local).shape[1]
+        c = _caches(S, n_ctx=n, lens=tuple(lens))
+        pp = (ctypes.c_float * n)(*p)
+        assert S._lib.samkv_block_filter_count(ctypes.byref(c), block, pp, n_init, n_local) == want, (lens, block, p)
+    c = _caches(S, lens=(10, 8))
+    assert S._lib.samkv_block_filter_count(ctypes.byref(c), 4, (ctypes.c_float * 2)(0.5, 0.5), 1, 0) == 0   # short last block
+
+
 def test_workspace_bytes(S):
     assert S.samkv_workspace_bytes(10, 32, 8, 128, 32, 1540) > 0
     assert S.samkv_workspace_bytes(0, 32, 8, 128, 32, 1540) == 0
@@ -120,6 +138,12 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_block_select(fake, ctypes.byref(ok), 4, pf, 1, 1, fake, None, cu, None, 0, None) == -3
     # a short last block that only some heads might keep: rejected (10 tokens in blocks of 4, no local block forced)
     assert L.samkv_block_select(fake, ctypes.byref(ragged), 4, pf, 1, 0, fake, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_block_select_filter(fake, ctypes.byref(ragged), 4, pf, 1, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_block_select_filter(fake, ctypes.byref(ok), 4, pf, 1, 1, fake, None, 0, None) == -3
+    assert L.samkv_block_select_filter(fake, ctypes.byref(ok), 4, pf, 1, 1, None, fake, 1 << 20, None) == -1
+    assert L.samkv_gather_g(ctypes.byref(ok), None, 4, fake, fake, None) == -1
+    assert L.samkv_gather_g(ctypes.byref(ok), fake, 0, fake, fake, None) == -1
+    assert L.samkv_gather_q_g(ctypes.byref(ok), qp, fake, 4, None, None) == -1
     assert L.samkv_gather_q_v(ctypes.byref(ok), qp, fake, None, fake, None) == -1
     assert L.samkv_gather_q_v(ctypes.byref(ok), qp, fake, (ctypes.c_int32 * 3)(0, 9, 12), fake, None) == -1   # 9 > len 8
     assert L.samkv_gather_v(ctypes.byref(ok), fake, (ctypes.c_int32 * 3)(1, 2, 3), fake, fake, None) == -1

@@ -393,3 +393,49 @@ def test_select_full_length_row_of_equal_scores(S):
         idx = torch.full((1, int(cu[-1])), -1, dtype=torch.int32, device="cuda")
         assert S.samkv_topk_select(dev, caches, ratio, n_sink, n_local, idx, None) == cu.tolist()
         assert np.array_equal(idx.cpu().numpy(), want)
+
+
+def test_block_filter_across_documents_and_gather_by_global_positions(S):
+    """Second filter of Sec. 3.2 (min-max reading, decisions in float32 on both sides): surviving blocks per KV head
+    as global token positions, bit-exact; K/V and Q-cache gathers by global position, bit-exact."""
+    import torch
+    lens = [700, 130, 64, 1500, 33, 4096 + 17]
+    x = synth.make_small(72, "bf16", lens, 8, 2, 128, 4, 8)
+    q_hat = O.personalized_query(x.q_tok, x.q_loc, len(lens))
+    caches = H.upload_caches(x)
+    q_cache = synth.make_q_cache(x.workload, 0, x.lens)
+    dev_q = [H.to_dev(q, "bf16") for q in q_cache]
+    for block, n_init, n_local, p in ((64, 1, 2, [0.25, 0.5, 0.3, 0.1, 1.0, 0.05]), (16, 2, 1, [0.0, 1.0, 0.5, 0.2, 0.4, 0.15]),
+                                      (16, 0, 1, [0.0, 0.0, 0.0, 0.0, 0.0, 0.0]), (8, 1, 1, [1.0] * 6)):
+        b32 = [b.astype(np.float32) for b in O.block_scores(q_hat, x.k, block)]
+        want = O.block_filter([b.astype(np.float64) for b in b32], lens, block, p, n_init, n_local)
+        m = want.shape[1]
+        assert S.samkv_block_filter_count(caches, block, p, n_init, n_local) == m
+        gidx = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(S.samkv_block_workspace_bytes(caches, block), dtype=torch.uint8, device="cuda")
+        S.samkv_block_select_filter(torch.from_numpy(np.concatenate(b32, axis=1)).cuda(), caches, block, p, n_init,
+                                    n_local, gidx, ws)
+        assert np.array_equal(gidx.cpu().numpy(), want), (block, n_init, n_local)
+        k_c = torch.zeros((2, m, 128), dtype=torch.bfloat16, device="cuda")
+        v_c = torch.zeros_like(k_c)
+        S.samkv_gather_g(caches, gidx, k_c, v_c)
+        assert np.array_equal(k_c.float().cpu().numpy(), O.gather_global(x.k, want))
+        assert np.array_equal(v_c.float().cpu().numpy(), O.gather_global(x.v, want))
+        q_rec = torch.zeros((8, m, 128), dtype=torch.bfloat16, device="cuda")
+        S.samkv_gather_q_g(caches, dev_q, gidx, q_rec)
+        assert np.array_equal(q_rec.float().cpu().numpy(), O.gather_global(q_cache, want, group=4))
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64)])
+def test_gather_by_global_positions_other_row_sizes(S, dtype, d):
+    import torch
+    x = synth.make_small(73, dtype, [300, 77, 1025, 5], 8, 2, d, 3, 2)
+    rng = np.random.default_rng(73)
+    total = sum(x.lens)
+    gidx = np.sort(rng.choice(total, size=(2, 501), replace=True), axis=1).astype(np.int32)   # repeats are legal
+    caches = H.upload_caches(x)
+    k_c = torch.zeros((2, 501, d), dtype=H.torch_dtype(dtype), device="cuda")
+    v_c = torch.zeros_like(k_c)
+    S.samkv_gather_g(caches, torch.from_numpy(gidx).cuda(), k_c, v_c)
+    assert np.array_equal(k_c.float().cpu().numpy(), O.gather_global(x.k, gidx))
+    assert np.array_equal(v_c.float().cpu().numpy(), O.gather_global(x.v, gidx))

@@ -572,3 +572,56 @@ def test_block_select_hand_values_and_token_granularity_special_case():
     # heads that would keep different token counts are refused (short last block neither forced nor dropped by all)
     with pytest.raises(AssertionError):
         O.block_select([np.array([[0.0, 1.0, 5.0, -3.0], [9.0, 2.0, 1.0, 9.0]])], [10], 3, [0.5], 1, 0)
+
+
+def test_block_filter_hand_values_and_reductions():
+    # Two documents, blocks of 2 tokens, first and last block forced, every middle block retrieved (p = 1).
+    #   document 0: 5 blocks, scores 9 1 5 3 9 -> candidates 1, 2, 3 with min-max normalised scores 0, 1, 0.5
+    #   document 1: 4 blocks, scores 0 10 20 0 -> candidates 1, 2 with normalised scores 0, 1
+    # 5 candidates over 2 documents -> 3 survive: block 2 of each document (1.0) and block 3 of document 0 (0.5).
+    b = [np.array([[9.0, 1, 5, 3, 9]]), np.array([[0.0, 10, 20, 0]])]
+    got = O.block_filter(b, [10, 8], 2, [1.0, 1.0], 1, 1)
+    assert got.tolist() == [[0, 1, 4, 5, 6, 7, 8, 9, 10, 11, 14, 15, 16, 17]]
+    # the scale of a document's scores does not matter (that is what the normalisation is for) ...
+    b2 = [b[0] * 1000.0 - 7.0, b[1] * 0.001 + 3.0]
+    assert np.array_equal(O.block_filter(b2, [10, 8], 2, [1.0, 1.0], 1, 1), got)
+    # ... a single document keeps everything it retrieved (C / 1 = C): the filter reduces to block_select
+    r = rng(92)
+    bs = [r.standard_normal((3, 12))]
+    idx, cu = O.block_select(bs, [12 * 8 - 3], 8, [0.4], 1, 2)
+    assert np.array_equal(O.block_filter(bs, [12 * 8 - 3], 8, [0.4], 1, 2), idx)
+    # ... and with several documents: forced blocks always survive, the survivors are a subset of what the
+    # per-document selection retrieved, and their number is forced + ceil(C / N) blocks
+    lens, block = [200, 64, 333, 1000], 16
+    bs = [r.standard_normal((2, -(-L // block))) for L in lens]
+    p = [0.5, 0.3, 0.0, 0.2]
+    idx, cu = O.block_select(bs, lens, block, p, 1, 2)
+    got = O.block_filter(bs, lens, block, p, 1, 2)
+    cu_len = np.concatenate([[0], np.cumsum(lens)])
+    n_cand = sum(O.kept_count_mid(-(-L // block), pi, 1, 2) - 3 for L, pi in zip(lens, p))
+    forced_tokens = sum(16 + (L - (-(-L // block) - 2) * block) for L in lens)
+    assert got.shape[1] == forced_tokens + -(-n_cand // 4) * block
+    for g in range(2):
+        retrieved = set()
+        for i in range(4):
+            retrieved |= {int(cu_len[i] + t) for t in idx[g, cu[i]:cu[i + 1]]}
+            forced = set(range(cu_len[i], cu_len[i] + 16)) | set(range(cu_len[i] + (-(-lens[i] // block) - 2) * block, cu_len[i + 1]))
+            assert forced <= set(got[g].tolist())
+        assert set(got[g].tolist()) <= retrieved
+        assert np.all(np.diff(got[g]) > 0)
+
+
+def test_gather_global_matches_per_document_gather():
+    r = rng(93)
+    lens = [9, 4, 17]
+    k = [r.standard_normal((2, L, 4)) for L in lens]
+    v = [r.standard_normal((2, L, 4)) for L in lens]
+    idx, cu = O.select([r.standard_normal((2, L)) for L in lens], 0.5)
+    cu_len = np.concatenate([[0], np.cumsum(lens)])
+    gidx = idx.copy()
+    for i in range(3):
+        gidx[:, cu[i]:cu[i + 1]] += cu_len[i]
+    k_c, v_c = O.gather(k, v, idx, cu)
+    assert np.array_equal(O.gather_global(k, gidx), k_c) and np.array_equal(O.gather_global(v, gidx), v_c)
+    q = [r.standard_normal((6, L, 4)) for L in lens]
+    assert np.array_equal(O.gather_global(q, gidx, group=3), O.gather_q(q, idx, cu))
