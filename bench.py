@@ -154,6 +154,44 @@ def at_scale(samkv, iters=5):
     ss_ms = res["score"]["ms"] + res["select"]["ms"]
     ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / ss_ms / 1e6
     res["score+select"] = {"ms": round(ss_ms, 4), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4)}
+
+    # block-level variant of the selection (64-token blocks, 1 initial + 2 local blocks forced, per-document share
+    # 0.15 of the middle blocks), with and without the cross-document filter, and the gather that follows each
+    block, p = 64, [0.15] * w.n_ctx
+    nb = sum(-(-n // block) for n in w.lens)
+    bs = torch.empty((w.n_kv_heads, nb), dtype=torch.float32, device="cuda")
+    bws = torch.empty(samkv.samkv_block_workspace_bytes(caches, block), dtype=torch.uint8, device="cuda")
+    samkv.samkv_block_scores(buf.scores, caches, block, bs)
+    mb = samkv.samkv_block_select_count(caches, block, p, 1, 2)
+    idx_b = torch.empty((w.n_kv_heads, mb), dtype=torch.int32, device="cuda")
+    cu = samkv.samkv_block_select(bs, caches, block, p, 1, 2, idx_b, None, bws)
+    mf = samkv.samkv_block_filter_count(caches, block, p, 1, 2)
+    gidx = torch.empty((w.n_kv_heads, mf), dtype=torch.int32, device="cuda")
+    kb, vb = (torch.empty((w.n_kv_heads, mb, w.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    kf, vf = (torch.empty((w.n_kv_heads, mf, w.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    row = w.head_dim * 2
+    bcalls = {
+        "block_scores": (lambda: samkv.samkv_block_scores(buf.scores, caches, block, bs), 4 * w.n_kv_heads * (sum(w.lens) + nb)),
+        "block_select": (lambda: samkv.samkv_block_select(bs, caches, block, p, 1, 2, idx_b, None, bws), 4 * w.n_kv_heads * (nb + mb)),
+        "gather_v": (lambda: samkv.samkv_gather_v(caches, idx_b, cu, kb, vb), w.n_kv_heads * mb * (4 * row + 4)),
+        "block_select_filter": (lambda: samkv.samkv_block_select_filter(bs, caches, block, p, 1, 2, gidx, bws), 4 * w.n_kv_heads * (nb + mf)),
+        "gather_g": (lambda: samkv.samkv_gather_g(caches, gidx, kf, vf), w.n_kv_heads * mf * (4 * row + 4)),
+    }
+    blk = {"block": block, "kept_tokens": mb, "kept_tokens_after_filter": mf}
+    for name, (fn, nbytes) in bcalls.items():
+        fn()
+        torch.cuda.synchronize()
+        ev = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
+        blk[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    res["block_level"] = blk
     return res
 
 

@@ -163,6 +163,10 @@ int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t
                        int32_t n_init_blocks, int32_t n_local_blocks, int32_t* idx, int32_t* cu_k_dev,
                        int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream);
 
+/* Tokens per KV head that samkv_block_select keeps, M (host arithmetic); 0 for invalid arguments. */
+int32_t samkv_block_select_count(const samkv_caches* caches, int32_t block, const float* p,
+                                 int32_t n_init_blocks, int32_t n_local_blocks);
+
 /* Sec. 3.2, second filter across documents, on top of samkv_block_select.  Per KV head: the candidates are the
  * middle blocks that the per-document selection retrieved; each document's candidate scores are normalised, the
  * candidates of all documents are compared, and keep = ceil(candidates / n_ctx) of them survive (the paper: the

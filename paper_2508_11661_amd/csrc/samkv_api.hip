@@ -371,6 +371,16 @@ int samkv_block_select(const float* bscores, const samkv_caches* caches, int32_t
   return dev(e);
 }
 
+int32_t samkv_block_select_count(const samkv_caches* caches, int32_t block, const float* p, int32_t n_init_blocks,
+                                 int32_t n_local_blocks) {
+  Shape s;
+  BlockPlan bp;
+  if (check_caches(caches, false, false, &s) != SAMKV_OK ||
+      block_plan(caches, s, block, p, n_init_blocks, n_local_blocks, &bp) != SAMKV_OK)
+    return 0;
+  return bp.cu_k.v[s.n_ctx];
+}
+
 int32_t samkv_block_filter_count(const samkv_caches* caches, int32_t block, const float* p, int32_t n_init_blocks,
                                  int32_t n_local_blocks) {
   Shape s;

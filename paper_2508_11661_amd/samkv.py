@@ -20,7 +20,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
            "samkv_score", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
-           "samkv_block_select_filter", "samkv_block_filter_count", "samkv_gather_g", "samkv_gather_q_g",
+           "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
            "samkv_kv_update")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
@@ -71,6 +71,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_block_select.argtypes = [vp, cp, i32, ctypes.POINTER(f32), i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_block_select_filter.restype = ctypes.c_int
     lib.samkv_block_select_filter.argtypes = [vp, cp, i32, ctypes.POINTER(f32), i32, i32, vp, vp, sz, vp]
+    lib.samkv_block_select_count.restype = i32
+    lib.samkv_block_select_count.argtypes = [cp, i32, ctypes.POINTER(f32), i32, i32]
     lib.samkv_block_filter_count.restype = i32
     lib.samkv_block_filter_count.argtypes = [cp, i32, ctypes.POINTER(f32), i32, i32]
     lib.samkv_gather_g.restype = ctypes.c_int
@@ -184,6 +186,7 @@ def samkv_topk_select(scores: torch.Tensor, caches: Caches, ratio: float, n_sink
     """idx [Hkv, M] int32 <- kept positions; returns the host prefix sums cu_k (length n_ctx + 1)."""
     cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
     assert idx.dtype == torch.int32
+    assert tuple(idx.shape) == (caches.n_kv_heads, sum(samkv_kept_count(n, ratio) for n in caches.lens))
     _check(_lib.samkv_topk_select(_ptr(scores), ctypes.byref(caches.c), ratio, n_sink, n_local, _ptr(idx),
                                   _ptr(cu_k_dev), cu_k_host, _ptr(ws),
                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
@@ -209,6 +212,8 @@ def samkv_topk_select_v(scores: torch.Tensor, caches: Caches, p: Sequence[float]
     """Selection with one middle-segment share per document; returns the host prefix sums cu_k."""
     cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
     pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    assert idx.dtype == torch.int32 and tuple(idx.shape) == (
+        caches.n_kv_heads, sum(max(0, samkv_kept_count_mid(n, pi, n_sink, n_local)) for n, pi in zip(caches.lens, p)))
     _check(_lib.samkv_topk_select_v(_ptr(scores), ctypes.byref(caches.c), pp, n_sink, n_local, _ptr(idx),
                                     _ptr(cu_k_dev), cu_k_host, None, 0, _stream()), "samkv_topk_select_v")
     return list(cu_k_host)
@@ -231,6 +236,12 @@ def samkv_block_workspace_bytes(caches: Caches, block: int) -> int:
     return int(_lib.samkv_block_workspace_bytes(ctypes.byref(caches.c), block))
 
 
+def samkv_block_select_count(caches: Caches, block: int, p: Sequence[float], n_init_blocks: int,
+                             n_local_blocks: int) -> int:
+    pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
+    return int(_lib.samkv_block_select_count(ctypes.byref(caches.c), block, pp, n_init_blocks, n_local_blocks))
+
+
 def samkv_block_select(bscores: torch.Tensor, caches: Caches, block: int, p: Sequence[float], n_init_blocks: int,
                        n_local_blocks: int, idx: torch.Tensor, cu_k_dev: Optional[torch.Tensor],
                        ws: torch.Tensor) -> List[int]:
@@ -238,6 +249,8 @@ def samkv_block_select(bscores: torch.Tensor, caches: Caches, block: int, p: Seq
     cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
     pp = (ctypes.c_float * caches.n_ctx)(*[float(x) for x in p])
     assert idx.dtype == torch.int32 and bscores.dtype == torch.float32
+    m = samkv_block_select_count(caches, block, p, n_init_blocks, n_local_blocks)
+    assert m == 0 or tuple(idx.shape) == (caches.n_kv_heads, m), "idx must be [Hkv, samkv_block_select_count(...)]"
     _check(_lib.samkv_block_select(_ptr(bscores), ctypes.byref(caches.c), block, pp, n_init_blocks, n_local_blocks,
                                    _ptr(idx), _ptr(cu_k_dev), cu_k_host, _ptr(ws), ws.numel() * ws.element_size(),
                                    _stream()), "samkv_block_select")
