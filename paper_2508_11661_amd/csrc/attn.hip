@@ -39,22 +39,29 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
 // ------------------------------------------------------------------------------------------ bf16
-template <int D, int NW_>
+// NW waves = RG row groups (32 query rows each) x KG key groups.  With KG = 2 a step stages 128 keys and the two
+// key groups of a row group each take 64 of them, so a causal row tile walks its keys in half as many sequential
+// steps; the two partial results meet through LDS at the end.  That is for short problems, where the longest row
+// tile's chain of steps, not the total work, sets the kernel's duration.
+template <int D, int NW_, int KG_ = 1>
 struct Bf16Cfg {
-  static constexpr int NW = NW_, NT = 64 * NW;
-  static constexpr int BQ = 32 * NW, BK = 64;
+  static constexpr int NW = NW_, NT = 64 * NW, KG = KG_, RG = NW / KG;
+  static constexpr int BQ = 32 * RG, BK = 64, BKT = BK * KG;
   static constexpr int KSTR = D * 2 + 16;  // bytes per K row in LDS (pad: 16 rows hit 64 distinct banks)
   static constexpr int VSTR = D * 2 + 64;  // bytes per V row in LDS: the 4 rows x 32 B of a transposing read fall in disjoint bank ranges
-  static constexpr int TILE_BYTES = BK * (KSTR + VSTR);
+  static constexpr int TILE_BYTES = BKT * (KSTR + VSTR);
   static constexpr int LDS_BYTES = 2 * TILE_BYTES;
-  static constexpr int CHUNKS = (BK * D * 2 / 16) / NT;  // 16-byte chunks per thread per tile and tensor
+  static constexpr int CHUNKS = (BKT * D * 2 / 16) / NT;  // 16-byte chunks per thread per tile and tensor
+  static constexpr int MERGE_BYTES = RG * 64 * (D / 32 * 16 + 2) * 4;  // one key group's state per row group
+  static_assert(KG == 1 || MERGE_BYTES <= LDS_BYTES, "the merge reuses the tile buffers");
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
-  using C = Bf16Cfg<D, NW>;
+template <int D, bool CAUSAL, int NW, int KG = 1>
+__global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs a) {
+  using C = Bf16Cfg<D, NW, KG>;
+  static_assert(KG == 1 || KG == 2, "one or two key groups");
   constexpr int ND = D / 16;   // k-steps of the S^T product
   constexpr int NV = D / 32;   // 32-row blocks of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -73,11 +80,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
   const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + C::BQ) : min(a.m, kv_begin + a.chunk);
-  const int n_tiles = (kv_end - kv_begin + C::BK - 1) / C::BK;
+  const int n_tiles = (kv_end - kv_begin + C::BKT - 1) / C::BKT;
 
-  const int r = q0 + wave * 32 + rw;
+  const int rg = wave % C::RG, kg = wave / C::RG;  // row group, key group
+  const int r = q0 + rg * 32 + rw;
   const int r_c = min(r, a.rows - 1);
-  const int wave_first = q0 + wave * 32, wave_last = wave_first + 31;
+  const int wave_first = q0 + rg * 32, wave_last = wave_first + 31;
 
   bf16x8 bq[ND];
   {
@@ -97,10 +105,10 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
   for (int i = 0; i < C::CHUNKS; ++i) voff[i] = (uint32_t)((t / CPR + i * RSTEP) * (D * 2) + (t % CPR) * 16);
   u32x4 rk[C::CHUNKS], rv[C::CHUNKS];
   auto load_tile = [&](int tile) {
-    const int k0 = kv_begin + tile * C::BK;
+    const int k0 = kv_begin + tile * C::BKT;
     const char* kt = kbase + (size_t)k0 * (D * 2);
     const char* vt = vbase + (size_t)k0 * (D * 2);
-    if (k0 + C::BK <= a.m) {
+    if (k0 + C::BKT <= a.m) {
 #pragma unroll
       for (int i = 0; i < C::CHUNKS; ++i) {
         rk[i] = *reinterpret_cast<const u32x4*>(kt + voff[i]);
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
   };
   auto store_tile = [&](int buf) {
     char* sk = smem + buf * C::TILE_BYTES;
-    char* sv = sk + C::BK * C::KSTR;
+    char* sv = sk + C::BKT * C::KSTR;
 #pragma unroll
     for (int i = 0; i < C::CHUNKS; ++i) {
       const int c = t + C::NT * i;
@@ -144,14 +152,14 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
   __syncthreads();
 
   for (int tile = 0; tile < n_tiles; ++tile) {
-    const int k0 = kv_begin + tile * C::BK;
+    const int k0 = kv_begin + tile * C::BKT + kg * C::BK;  // first key of this wave's 64 in the staged tile
     const bool more = tile + 1 < n_tiles;
     if (more) load_tile(tile + 1);
 
-    const bool active = !CAUSAL || k0 <= wave_last;
+    const bool active = (!CAUSAL || k0 <= wave_last) && (KG == 1 || k0 < kv_end);
     if (active) {
-      const char* sk = smem + (tile & 1) * C::TILE_BYTES;
-      const char* sv = sk + C::BK * C::KSTR;
+      const char* sk = smem + (tile & 1) * C::TILE_BYTES + kg * C::BK * C::KSTR;
+      const char* sv = smem + (tile & 1) * C::TILE_BYTES + C::BKT * C::KSTR + kg * C::BK * C::VSTR;
       f32x16 s[2];
       {
         // all K fragments of the tile are requested before the first product, so the LDS latency is
@@ -240,6 +248,32 @@ __global__ __launch_bounds__(64 * NW, 2) void k_attn_bf16(AttnArgs a) {
     }
     if (more) store_tile((tile + 1) & 1);
     __syncthreads();
+  }
+
+  if (KG == 2) {
+    // the second key group hands its running maximum, row sum and accumulator to the first through LDS
+    // (element e of lane l at word e * 64 + l: conflict-free), which rescales both to the common maximum
+    float* mg = reinterpret_cast<float*>(smem) + rg * (64 * (NV * 16 + 2)) + lane;
+    if (kg == 1) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) mg[(i * 16 + j) * 64] = o[i][j];
+      mg[(NV * 16) * 64] = m_run;
+      mg[(NV * 16 + 1) * 64] = l_run;
+    }
+    __syncthreads();
+    if (kg == 1) return;
+    const float m1 = mg[(NV * 16) * 64], l1 = mg[(NV * 16 + 1) * 64];
+    const float m_new = fmaxf(m_run, m1);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float a0 = __builtin_amdgcn_exp2f(m_run - m_use), a1 = __builtin_amdgcn_exp2f(m1 - m_use);
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[i][j] = o[i][j] * a0 + mg[(i * 16 + j) * 64] * a1;
+    l_run = l_run * a0 + l1 * a1;
+    m_run = m_new;
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -698,19 +732,19 @@ AttnArgs make_args(const AttnLaunch& l) {
   return a;
 }
 
-template <int D, bool CAUSAL, int NW>
+template <int D, bool CAUSAL, int NW, int KG = 1>
 hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
-  using C = Bf16Cfg<D, NW>;
+  using C = Bf16Cfg<D, NW, KG>;
   static bool attr_set = false;  // per process; the attribute belongs to the function, not the stream
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   AttnArgs a = make_args(l);
   dim3 grid(l.n_batch, (l.rows + C::BQ - 1) / C::BQ, a.n_split);
-  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW, KG>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -736,7 +770,13 @@ hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
   if constexpr (D == 128) {
     if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16_dma<CAUSAL>(l, s);
   }
-  return attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8 ? run_bf16<D, CAUSAL, 8>(l, s) : run_bf16<D, CAUSAL, 4>(l, s);
+  if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16<D, CAUSAL, 8>(l, s);
+  // short causal problems (at most two workgroups per compute unit): 128 rows per workgroup as with four waves, but
+  // two key groups halve the chain of steps of the longest row tile, which is what such a launch waits for
+  if constexpr (CAUSAL) {
+    if (l.rows > 256 && (long long)l.n_batch * ((l.rows + 127) / 128) <= 512) return run_bf16<D, CAUSAL, 8, 2>(l, s);
+  }
+  return run_bf16<D, CAUSAL, 4>(l, s);
 }
 
 template <int D, bool CAUSAL>

@@ -34,6 +34,9 @@ def _rows(m, n, seed):
     ("bf16", 128, 1024, 8, 129), ("bf16", 128, 1024, 8, 200), ("bf16", 128, 512, 8, 300), ("bf16", 128, 64, 8, 4200),
     ("bf16", 128, 128, 16, 2049), ("bf16", 64, 64, 8, 4200), ("bf16", 64, 8, 2, 700), ("bf16", 128, 8, 8, 700),
     ("f32", 128, 4, 2, 150), ("f32", 64, 8, 1, 97),
+    # few workgroups and more than 256 rows: the variant whose two key groups split every 128-key step
+    ("bf16", 128, 32, 8, 1540), ("bf16", 128, 4, 2, 257), ("bf16", 128, 4, 4, 321), ("bf16", 64, 16, 4, 449),
+    ("bf16", 128, 2, 1, 385), ("bf16", 64, 2, 2, 2048),
 ])
 def test_recompute_attention_shapes(dtype, d, hq, hkv, m):
     import torch
