@@ -1,7 +1,7 @@
 // samkv_score: personalized query vectors (Sec. 3.1, Eq. 1) and the inner product of every cached key
 // with the vector of its own document (Sec. 3.2).
 //
-// Four launches on one stream:
+// Four launches on one stream (short inputs: k_prologue replaces the first three, see there):
 //   k_pool    mean-pools the user query's Q rows (Q_que) and every document's local Q cache (Q_loc_j).
 //   k_bias    per query head: |cos(Q_que, Q_loc_j)| for every j and the weighted sum over all documents.
 //   k_qtilde  Eq. 1 for the query heads of a KV group, folded into one vector per document (the mean
@@ -151,13 +151,135 @@ __global__ void k_qtilde(const float* que, const float* bias, const float* loc, 
   qt[((size_t)i * hkv + g) * d + c] = acc / (float)G;
 }
 
+// The three launches above in one, for short inputs (one workgroup of 16 waves per query head; the head's local
+// Q caches of all documents pass through that one workgroup, so this is for inputs of up to about a megabyte per
+// head, where launch latency and not bandwidth is what the three launches cost).  Writes Eq. 1 per QUERY head,
+// qhat[i][h][:]; k_score folds the heads of a KV group.
+//   1. Q_que[h]: the 16 waves split the user query's rows; partial sums meet in LDS.
+//   2. wave w takes documents w, w + 16, ...: mean of the document's local rows, |cos| with Q_que.
+//   3. bias = sum_j w_j Q_loc_j, then Q^_i = Q_que + (bias - w_i Q_loc_i) / (N - 1).
+template <bool BF16, int D>
+__global__ __launch_bounds__(1024) void k_prologue(const void* q_tok, int n_q_tok, const void* q_loc, int w_loc, int n_ctx,
+                                                   int hq, int with_bias, float* qhat) {
+  constexpr int EPL = BF16 ? 8 : 4;
+  constexpr int LPR = D / EPL;   // lanes per row
+  constexpr int RPW = 64 / LPR;  // rows per wave step
+  constexpr size_t ROW_BYTES = (size_t)D * (BF16 ? 2 : 4);
+  extern __shared__ float sm[];
+  float* s_que = sm;                 // [D]
+  float* s_bias = sm + D;            // [D]
+  float* red = sm + 2 * D;           // [16][D]
+  float* s_w = red + 16 * D;         // [n_ctx]
+  float* s_loc = s_w + SAMKV_MAX_CTX;  // [n_ctx][D]
+  const int h = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int sub = lane % LPR, rgp = lane / LPR;
+
+  // acc += rows first, first + step, ... (< n_rows) of `src`, sixteen 16-byte loads in flight per lane
+  auto add_rows = [&](const char* src, int first, int step, int n_rows, float* acc) {
+    constexpr int U = 16;
+    for (int r0 = first; r0 < n_rows; r0 += U * step) {
+      u32x4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = r0 + u * step;
+        x[u] = *reinterpret_cast<const u32x4*>(src + (size_t)(r < n_rows ? r : n_rows - 1) * ROW_BYTES);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float f[EPL];
+        unpack16<BF16>(x[u], f);
+        const float keep = (r0 + u * step < n_rows) ? 1.f : 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(f[e], keep, acc[e]);
+      }
+    }
+  };
+  // sum over the row groups of a wave: lanes that differ in the bits above log2(LPR)
+  auto fold_rows = [&](float* acc) {
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
+  };
+  {
+    const char* src = static_cast<const char*>(q_tok) + (size_t)h * n_q_tok * ROW_BYTES + sub * 16;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    add_rows(src, wave * RPW + rgp, 16 * RPW, n_q_tok, acc);
+    fold_rows(acc);
+    if (rgp == 0)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) red[wave * D + sub * EPL + e] = acc[e];
+  }
+  __syncthreads();
+  if (t < D) {
+    float v = 0.f;
+    for (int w = 0; w < 16; ++w) v += red[w * D + t];
+    s_que[t] = v / (float)n_q_tok;
+  }
+  __syncthreads();
+  if (with_bias) {
+    float qv[EPL], na = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      qv[e] = s_que[sub * EPL + e];
+      na = fmaf(qv[e], qv[e], na);
+    }
+    na = group_sum<LPR>(na);
+    for (int j = wave; j < n_ctx; j += 16) {
+      const char* src = static_cast<const char*>(q_loc) + ((size_t)j * hq + h) * w_loc * ROW_BYTES + sub * 16;
+      float acc[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+      add_rows(src, rgp, RPW, w_loc, acc);
+      fold_rows(acc);
+      float dot = 0.f, nb = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        acc[e] /= (float)w_loc;
+        dot = fmaf(qv[e], acc[e], dot);
+        nb = fmaf(acc[e], acc[e], nb);
+      }
+      dot = group_sum<LPR>(dot);
+      nb = group_sum<LPR>(nb);
+      if (rgp == 0)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_loc[j * D + sub * EPL + e] = acc[e];
+      if (lane == 0) {
+        const float ra = sqrtf(na), rb = sqrtf(nb);
+        s_w[j] = (ra < 1e-20f || rb < 1e-20f) ? 0.f : fabsf(dot / (ra * rb));
+      }
+    }
+    __syncthreads();
+    const int c = t % D, sl = t / D;
+    constexpr int NS = 1024 / D;
+    float acc = 0.f;
+    for (int j = sl; j < n_ctx; j += NS) acc = fmaf(s_w[j], s_loc[j * D + c], acc);
+    red[sl * D + c] = acc;
+    __syncthreads();
+    if (t < D) {
+      float b = 0.f;
+      for (int s2 = 0; s2 < NS; ++s2) b += red[s2 * D + t];
+      s_bias[t] = b;
+    }
+    __syncthreads();
+  }
+  for (int x = t; x < n_ctx * D; x += 1024) {
+    const int i = x / D, c = x % D;
+    float v = s_que[c];
+    if (with_bias) v += (s_bias[c] - s_w[i] * s_loc[i * D + c]) / (float)(n_ctx - 1);
+    qhat[((size_t)i * hq + h) * D + c] = v;
+  }
+}
+
 // One block = 4 waves; a wave loads 16 x 16 bytes per lane up front (two batches of NB rows groups),
 // so about 16 KB per wave is in flight.  LPR lanes share one key row; their partial dot products are
 // combined with DPP moves, and lane (row group rg, sub < NB) stores row sub * RPL + rg of the batch:
 // 32 consecutive floats per wave store.
 template <bool BF16, int D>
-__global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, const float* qt, float* scores, int hkv,
-                                               int total_len) {
+__global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, const float* qsrc, int heads, int group,
+                                               float* scores, int total_len) {
   constexpr int EPL = BF16 ? 8 : 4;
   constexpr int LPR = D / EPL;
   constexpr int RPL = 64 / LPR;
@@ -173,11 +295,18 @@ __global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, con
   if (row0 >= L) return;
   const int lane = threadIdx.x & 63, sub = lane % LPR, rg = lane / LPR;
 
+  // the document's vector for this KV head: qsrc is [N][heads][D]; `group` consecutive heads are averaged
+  // (1 when the fold over the KV group has already been done, G when qsrc holds Eq. 1 per query head)
   float q[EPL];
   {
-    const float* qp = qt + ((size_t)i * hkv + g) * D + sub * EPL;
+    const float* qp = qsrc + ((size_t)i * heads + (size_t)g * group) * D + sub * EPL;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) q[e] = qp[e];
+    for (int e = 0; e < EPL; ++e) q[e] = 0.f;
+    for (int hh = 0; hh < group; ++hh)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) q[e] += qp[hh * D + e];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q[e] /= (float)group;
   }
   const char* base = static_cast<const char*>(kt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
   float* out = scores + (size_t)g * total_len + cu_len.v[i];
@@ -212,15 +341,25 @@ __global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, con
 template <bool BF16, int D>
 hipError_t run(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s) {
   const bool bias = a.q_loc != nullptr && a.n_ctx > 1;
+  constexpr int TILE = (64 / (D / (BF16 ? 8 : 4))) * 8 * 2 * 4;
+  dim3 gs((a.max_len + TILE - 1) / TILE, a.n_ctx, a.hkv);
+  // bytes of Q rows that pass through one query head's workgroup in the one-launch prologue
+  const size_t per_head = ((size_t)a.n_q_tok + (bias ? (size_t)a.n_ctx * a.w_loc : 0)) * D * (BF16 ? 2 : 4);
+  if (a.n_ctx <= 64 && per_head <= (1u << 20)) {
+    const size_t lds = (size_t)(2 * D + 16 * D + SAMKV_MAX_CTX + a.n_ctx * D) * sizeof(float);
+    hipLaunchKernelGGL((k_prologue<BF16, D>), dim3(a.hq), dim3(1024), lds, s, a.q_tok, a.n_q_tok, a.q_loc, a.w_loc, a.n_ctx,
+                       a.hq, bias ? 1 : 0, a.ws_loc);
+    hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_loc, a.hq, a.hq / a.hkv, a.scores,
+                       a.total_len);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((k_pool<BF16, D>), dim3(a.hq, bias ? a.n_ctx + 1 : 1), dim3(256), 0, s, a.q_tok, a.n_q_tok,
                      a.q_loc, a.w_loc, a.hq, a.ws_que, a.ws_loc);
   if (bias)
     hipLaunchKernelGGL(k_bias, dim3(a.hq), dim3(1024), 0, s, a.ws_que, a.ws_loc, a.ws_w, a.ws_base, a.n_ctx, a.hq, D);
   hipLaunchKernelGGL(k_qtilde, dim3(a.n_ctx, a.hkv), dim3(D), 0, s, a.ws_que, a.ws_base, a.ws_loc, a.ws_w, a.ws_qt,
                      a.n_ctx, a.hq, a.hkv, D, bias ? 1 : 0);
-  constexpr int TILE = (64 / (D / (BF16 ? 8 : 4))) * 8 * 2 * 4;
-  dim3 gs((a.max_len + TILE - 1) / TILE, a.n_ctx, a.hkv);
-  hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_qt, a.scores, a.hkv, a.total_len);
+  hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_qt, a.hkv, 1, a.scores, a.total_len);
   return hipGetLastError();
 }
 

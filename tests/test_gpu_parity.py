@@ -139,6 +139,15 @@ def test_single_document_and_no_local_cache(S, dtype):
     _stages(S, x, 0.5, use_bias=False)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_many_short_documents(S, dtype, d):
+    # more than 64 documents: Eq. 1 runs as separate pooling / bias / fold launches instead of the single launch
+    # that short inputs take; ragged lengths, a local Q cache of 5 rows
+    lens = [40 + (7 * i) % 90 for i in range(70)]
+    x = synth.make_small(17, dtype, lens, 8, 2, d, 6, 5)
+    _stages(S, x, 0.25)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_degenerate_sizes(S, dtype):
     # documents of one and two tokens, compacted cache of a handful of rows
