@@ -30,7 +30,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 FP32_VALU_PEAK_TFLOPS = 157.3
-KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")
+KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")          # the five entry points of the path
+STEP = ("score_select", "gather", "recompute_attn", "query_attn")                # what a step launches: the first two fused
 
 
 def algorithmic_work(w, lens, m, n_q_tok):
@@ -43,6 +44,8 @@ def algorithmic_work(w, lens, m, n_q_tok):
     return {
         "score": {"bytes": tot * hkv * (d * e + 4) + q_rows * d * e, "flops": 2 * d * tot * hkv},
         "select": {"bytes": tot * hkv * 4 + m * hkv * 4, "flops": 0},
+        # fused: K and the Q rows read once, only the kept positions written (the scores stay on chip)
+        "score_select": {"bytes": tot * hkv * d * e + q_rows * d * e + m * hkv * 4, "flops": 2 * d * tot * hkv},
         "gather": {"bytes": m * hkv * (4 * d * e + 4), "flops": 0},
         "recompute_attn": {"bytes": (2 * hq + 2 * hkv) * m * d * e + hq * m * (d + 1) * 4,
                            "flops": 4 * hq * d * m * (m + 1) // 2},
@@ -54,7 +57,7 @@ def algorithmic_work(w, lens, m, n_q_tok):
 def read_traffic(workload, kernel: str):
     """HBM bytes per launch (read + write) of a kernel, from the committed rocprofv3 --pmc summary of this
     workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
-    prefix = {"score": "k_score", "select": "k_select", "gather": "k_gather",
+    prefix = {"score": "k_score<", "select": "k_select", "gather": "k_gather", "score_select": "k_score_select",
               "recompute_attn": "k_attn_%s<%d, true" % (workload.dtype, workload.head_dim),
               "query_attn": "k_attn_%s<%d, false" % (workload.dtype, workload.head_dim)}[kernel]
     try:
@@ -156,8 +159,23 @@ def at_scale(samkv, iters=5):
                      "frac_hbm": round(work[name]["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
                      "frac_mfma": round(work[name]["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
     ss_ms = res["score"]["ms"] + res["select"]["ms"]
-    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / ss_ms / 1e6
+    ss_bytes = work["score"]["bytes"] + m * w.n_kv_heads * 4
+    ss_gbs = ss_bytes / ss_ms / 1e6
     res["score+select"] = {"ms": round(ss_ms, 4), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4)}
+    fused = lambda: samkv.samkv_score_select(caches, q_tok, q_loc, 0.15, 0, 0, None, buf.idx, buf.cu_k_dev, buf.ws)
+    fused()
+    torch.cuda.synchronize()
+    ev = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fused()
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
+    res["score_select_fused"] = {"ms": round(ms, 4), "GB/s": round(ss_bytes / ms / 1e6, 1),
+                                 "frac_hbm": round(ss_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
     # block-level variant of the selection (64-token blocks, 1 initial + 2 local blocks forced, per-document share
     # 0.15 of the middle blocks), with and without the cross-document filter, and the gather that follows each
@@ -258,14 +276,16 @@ def main() -> int:
         "recompute_attn": lambda s: samkv.samkv_recompute_attn(s["q_rec"], buf.k_c, buf.v_c, scale, buf.rec_out,
                                                                buf.rec_lse, buf.ws),
         "query_attn": lambda s: samkv.samkv_query_attn(s["q_tok"], buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws),
+        "score_select": lambda s: samkv.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, buf.idx,
+                                                           buf.cu_k_dev, buf.ws),
     }
 
-    def step(i, events=None, only=None):
+    def step(i, events=None, only=None, names=STEP):
         """One pass of the hot path.  `events`: dict name -> list of (start, end) HIP events on the launch stream,
         recorded around every call, or only around the call named `only`."""
         for l in range(n_layers):
             s = sets[(i * n_layers + l) % len(sets)]
-            for name in KERNELS:
+            for name in names:
                 if events is not None and (only is None or only == name):
                     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     a.record()
@@ -280,11 +300,11 @@ def main() -> int:
 
     # untimed: which call dominates (events around every call cost a few microseconds each, so the timed region
     # below carries them only around that one call)
-    probe = {name: [] for name in KERNELS}
+    probe = {name: [] for name in STEP}
     for i in range(3):
         step(i, probe)
     torch.cuda.synchronize()
-    dom = max(KERNELS, key=lambda n: mean_ms(probe[n][len(probe[n]) // 3:]))
+    dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 3:]))
 
     for i in range(args.warmup):
         step(i)
@@ -297,10 +317,11 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    # untimed again: every call bracketed, for the per-call table
-    events = {name: [] for name in KERNELS}
+    # untimed again: every call bracketed, for the per-call table (the step's fused call, then the five entry points)
+    events = {name: [] for name in STEP + KERNELS}
     for i in range(min(args.steps, 50)):
         step(args.warmup + args.steps + i, events)
+        step(args.warmup + args.steps + i, events, names=KERNELS)
     torch.cuda.synchronize()
     events[dom] = dom_events[dom]          # the dominant call's figure is the one from the timed region
 
@@ -335,7 +356,7 @@ def main() -> int:
 
     work = algorithmic_work(w, w.lens, m, w.n_q_tok)
     per_kernel = {}
-    for name in KERNELS:
+    for name in STEP + tuple(n for n in KERNELS if n not in STEP):
         ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
         gbs = work[name]["bytes"] / (ms * 1e-3) / 1e9
         tfl = work[name]["flops"] / (ms * 1e-3) / 1e12
@@ -348,7 +369,8 @@ def main() -> int:
     ss_ms = per_kernel["score"]["ms"] + per_kernel["select"]["ms"]
     ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / (ss_ms * 1e-3) / 1e9
     per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
-                                  "note": "the two calls as one K-streaming stage: score's bytes + the kept indices"}
+                                  "note": "the two separate calls as one K-streaming stage, for comparison with the "
+                                          "fused score_select call that the timed step launches"}
     if dom.endswith("attn") and w.dtype == "bf16":
         roof = {"kernel": dom, "bound": "mfma", "achieved": per_kernel[dom]["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS, 4)}

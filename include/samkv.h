@@ -112,6 +112,14 @@ int samkv_topk_select(const float* scores, const samkv_caches* caches, float rat
                       int32_t n_local, int32_t* idx, int32_t* cu_k_dev, int32_t* cu_k_host, void* ws,
                       size_t ws_bytes, void* stream);
 
+/* samkv_score and samkv_topk_select as one call that passes over K once: a workgroup owns one (document, KV head)
+ * row, keeps its scores on chip and selects from there.  Arguments as in the two calls; the kept positions are
+ * bit-identical to theirs.  `scores` may be NULL when the caller does not need them; documents longer than 8192
+ * tokens fall back to the two kernels and then need `scores` as their buffer (NULL is SAMKV_EINVAL there). */
+int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                       int32_t w_loc, float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx,
+                       int32_t* cu_k_dev, int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream);
+
 /* Sec. 3.2, dynamic Top-P (Eq. 2 and Eq. 3).  HOST arithmetic on a handful of scalars, no device work:
  *   P^(n)_i = (s_max - s_anc) / (s_max - s_min)  if s_min < s_anc <= s_max, else 0                  (Eq. 2)
  *   P_i     = mean over the n_layers stable layers of P^(n)_i                                        (Eq. 3)

@@ -42,6 +42,13 @@ struct ScoreLaunch {
   float* ws_qt;     // [N][Hkv][d]
 };
 hipError_t launch_score(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s);
+// Where the per-document vectors of Eq. 1 are after the prologue: [N][heads][d] float32, of which `group`
+// consecutive heads are averaged into the vector of one KV head.
+struct QuerySrc {
+  const float* q;
+  int heads, group;
+};
+hipError_t launch_score_prologue(const ScoreLaunch& a, hipStream_t s, QuerySrc* q);
 
 struct SelectLaunch {
   int n_ctx, hkv, max_len, total_len, m_total, n_sink, n_local;
@@ -50,6 +57,11 @@ struct SelectLaunch {
   int32_t* cu_k_dev;  // may be null
 };
 hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s);
+
+// Score and selection in one pass over K (rows of at most kFusedMaxLen tokens): a.scores may be null.
+constexpr int kFusedMaxLen = 8192;
+hipError_t launch_score_select(const ScoreLaunch& a, const SelectLaunch& sl, const PtrTable& k, const IntTable& cu_len,
+                               const IntTable& cu_k, hipStream_t s);
 
 hipError_t launch_block_scores(const float* scores, const IntTable& cu_len, const IntTable& cu_blk, int n_ctx, int hkv,
                                int total_len, int block, float* bscores, hipStream_t s);

@@ -1,0 +1,85 @@
+// samkv_score_select: the inner products of a document's keys with its personalized query (Sec. 3.2) and the
+// selection of the kept positions in ONE pass: a workgroup owns one (document, KV head) row, streams its K rows
+// once, keeps the scores in LDS and selects from there.  The scores never travel to HBM and back (unless the caller
+// asks for them), and the selection's barrier-bound passes of one workgroup overlap with the K streaming of its
+// neighbours on the compute unit.  Both halves are the device functions the separate kernels use, so the kept
+// positions are bit-identical to samkv_score followed by samkv_topk_select.
+#include "common.hpp"
+#include "kernels_core.hpp"
+
+namespace samkv {
+namespace {
+
+template <bool BF16, int D, int E, int NT>
+__global__ __launch_bounds__(NT) void k_score_select(PtrTable kt, IntTable cu_len, IntTable cu_k, const float* qsrc, int heads,
+                                                     int group, int total_len, int m_total, int n_ctx, int n_sink,
+                                                     int n_local, float* scores, int32_t* idx, int32_t* cu_k_dev) {
+  constexpr int EPL = BF16 ? 8 : 4;
+  constexpr int LPR = D / EPL;
+  constexpr int ROWS_PER_WAVE = (64 / LPR) * 8 * 2;
+  constexpr int NW = NT / 64;
+  constexpr size_t ROW_BYTES = (size_t)D * (BF16 ? 2 : 4);
+  extern __shared__ float s_sc[];  // the row's scores
+  __shared__ uint32_t cnt[2][NW];
+  __shared__ uint64_t wsum[NW];
+  const int i = blockIdx.x, g = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  if (cu_k_dev != nullptr && i == 0 && g == 0)
+    for (int n = t; n <= n_ctx; n += NT) cu_k_dev[n] = cu_k.v[n];
+  const int L = cu_len.v[i + 1] - cu_len.v[i];
+  const int k = cu_k.v[i + 1] - cu_k.v[i];
+  const int sub = lane % LPR;
+
+  float q[EPL];
+  fold_query<EPL>(qsrc + ((size_t)i * heads + (size_t)g * group) * D + sub * EPL, D, group, q);
+  const char* base = static_cast<const char*>(kt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
+  for (int row0 = wave * ROWS_PER_WAVE; row0 < L; row0 += NW * ROWS_PER_WAVE)
+    score_rows<BF16, D>(base, row0, L, q, [&](int row, float s) { s_sc[row] = s; });
+  __syncthreads();
+  if (scores != nullptr) {
+    float* out = scores + (size_t)g * total_len + cu_len.v[i];
+    for (int p = t; p < L; p += NT) out[p] = s_sc[p];
+  }
+
+  uint32_t key[E];
+  const int p0 = t * E;
+#pragma unroll
+  for (int e = 0; e < E; ++e) key[e] = (p0 + e < L) ? order_key(s_sc[p0 + e]) : 0u;
+  force_keys<E>(key, p0, L, n_sink, n_local);
+  select_from_keys<E, NT>(key, p0, L, k, idx + (size_t)g * m_total + cu_k.v[i], cnt, wsum);
+}
+
+template <bool BF16, int D, int E, int NT>
+hipError_t run(const ScoreLaunch& a, const SelectLaunch& sl, const QuerySrc& q, const PtrTable& k, const IntTable& cu_len,
+               const IntTable& cu_k, hipStream_t s) {
+  const size_t lds = (size_t)E * NT * sizeof(float);
+  hipLaunchKernelGGL((k_score_select<BF16, D, E, NT>), dim3(a.n_ctx, a.hkv), dim3(NT), lds, s, k, cu_len, cu_k, q.q, q.heads,
+                     q.group, a.total_len, sl.m_total, a.n_ctx, sl.n_sink, sl.n_local, a.scores, sl.idx, sl.cu_k_dev);
+  return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t run_len(const ScoreLaunch& a, const SelectLaunch& sl, const QuerySrc& q, const PtrTable& k,
+                   const IntTable& cu_len, const IntTable& cu_k, hipStream_t s) {
+  if (a.max_len <= 1024) return run<BF16, D, 4, 256>(a, sl, q, k, cu_len, cu_k, s);
+  if (a.max_len <= 4096) return run<BF16, D, 16, 256>(a, sl, q, k, cu_len, cu_k, s);
+  return run<BF16, D, 32, 256>(a, sl, q, k, cu_len, cu_k, s);
+}
+
+}  // namespace
+
+hipError_t launch_score_select(const ScoreLaunch& a, const SelectLaunch& sl, const PtrTable& k, const IntTable& cu_len,
+                               const IntTable& cu_k, hipStream_t s) {
+  if (a.max_len > kFusedMaxLen) {  // rows too long for LDS: the two kernels, through the caller's score buffer
+    if (a.scores == nullptr) return hipErrorInvalidValue;
+    hipError_t e = launch_score(a, k, cu_len, s);
+    return e != hipSuccess ? e : launch_select(sl, cu_len, cu_k, s);
+  }
+  QuerySrc q;
+  hipError_t e = launch_score_prologue(a, s, &q);
+  if (e != hipSuccess) return e;
+  if (a.dtype == SAMKV_BF16)
+    return a.d == 128 ? run_len<true, 128>(a, sl, q, k, cu_len, cu_k, s) : run_len<true, 64>(a, sl, q, k, cu_len, cu_k, s);
+  return a.d == 128 ? run_len<false, 128>(a, sl, q, k, cu_len, cu_k, s) : run_len<false, 64>(a, sl, q, k, cu_len, cu_k, s);
+}
+
+}  // namespace samkv

@@ -185,28 +185,57 @@ size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_head
   return (a > b ? a : b) + kAlign;
 }
 
+static int score_setup(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
+                       float* scores, void* ws, size_t ws_bytes, Shape* s, ScoreLaunch* a, PtrTable* kt) {
+  int rc = check_caches(caches, true, false, s);
+  if (rc != SAMKV_OK) return rc;
+  if (q_tok == nullptr || n_q_tok < 1 || (q_loc != nullptr && w_loc < 1)) return SAMKV_EINVAL;
+  const ScoreWs w = score_ws(s->n_ctx, s->hq, s->hkv, s->d);
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
+  memset(kt, 0, sizeof(*kt));
+  for (int i = 0; i < s->n_ctx; ++i) kt->p[i] = caches->k[i];
+  a->n_ctx = s->n_ctx; a->hq = s->hq; a->hkv = s->hkv; a->d = s->d; a->dtype = s->dtype;
+  a->n_q_tok = n_q_tok; a->w_loc = w_loc; a->max_len = s->max_len; a->total_len = s->total_len;
+  a->q_tok = q_tok; a->q_loc = q_loc; a->scores = scores;
+  char* base = static_cast<char*>(ws);
+  a->ws_que = reinterpret_cast<float*>(base + w.que);
+  a->ws_loc = reinterpret_cast<float*>(base + w.loc);
+  a->ws_w = reinterpret_cast<float*>(base + w.w);
+  a->ws_base = reinterpret_cast<float*>(base + w.base);
+  a->ws_qt = reinterpret_cast<float*>(base + w.qt);
+  return SAMKV_OK;
+}
+
 int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
                 float* scores, void* ws, size_t ws_bytes, void* stream) {
   Shape s;
-  int rc = check_caches(caches, true, false, &s);
-  if (rc != SAMKV_OK) return rc;
-  if (q_tok == nullptr || scores == nullptr || n_q_tok < 1 || (q_loc != nullptr && w_loc < 1)) return SAMKV_EINVAL;
-  const ScoreWs w = score_ws(s.n_ctx, s.hq, s.hkv, s.d);
-  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
-  PtrTable kt;
-  memset(&kt, 0, sizeof(kt));
-  for (int i = 0; i < s.n_ctx; ++i) kt.p[i] = caches->k[i];
   ScoreLaunch a;
-  a.n_ctx = s.n_ctx; a.hq = s.hq; a.hkv = s.hkv; a.d = s.d; a.dtype = s.dtype;
-  a.n_q_tok = n_q_tok; a.w_loc = w_loc; a.max_len = s.max_len; a.total_len = s.total_len;
-  a.q_tok = q_tok; a.q_loc = q_loc; a.scores = scores;
-  char* base = static_cast<char*>(ws);
-  a.ws_que = reinterpret_cast<float*>(base + w.que);
-  a.ws_loc = reinterpret_cast<float*>(base + w.loc);
-  a.ws_w = reinterpret_cast<float*>(base + w.w);
-  a.ws_base = reinterpret_cast<float*>(base + w.base);
-  a.ws_qt = reinterpret_cast<float*>(base + w.qt);
+  PtrTable kt;
+  if (scores == nullptr) return SAMKV_EINVAL;
+  int rc = score_setup(caches, q_tok, n_q_tok, q_loc, w_loc, scores, ws, ws_bytes, &s, &a, &kt);
+  if (rc != SAMKV_OK) return rc;
   return dev(launch_score(a, kt, s.cu_len, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
+                       float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx, int32_t* cu_k_dev,
+                       int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
+  Shape s;
+  ScoreLaunch a;
+  PtrTable kt;
+  if (idx == nullptr) return SAMKV_EINVAL;
+  int rc = score_setup(caches, q_tok, n_q_tok, q_loc, w_loc, scores, ws, ws_bytes, &s, &a, &kt);
+  if (rc != SAMKV_OK) return rc;
+  if (scores == nullptr && s.max_len > kFusedMaxLen) return SAMKV_EINVAL;
+  IntTable cu_k;
+  rc = kept_table(caches, ratio, n_sink, n_local, &cu_k);
+  if (rc != SAMKV_OK) return rc;
+  if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
+  SelectLaunch sl;
+  sl.n_ctx = s.n_ctx; sl.hkv = s.hkv; sl.max_len = s.max_len; sl.total_len = s.total_len;
+  sl.m_total = cu_k.v[s.n_ctx]; sl.n_sink = n_sink; sl.n_local = n_local;
+  sl.scores = scores; sl.idx = idx; sl.cu_k_dev = cu_k_dev;
+  return dev(launch_score_select(a, sl, kt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
 }
 
 static int select_common(const float* scores, const samkv_caches* caches, const Shape& s, const IntTable& cu_k,

@@ -8,40 +8,10 @@
 //             over the group is linear, so one pass over K serves all heads of the group).
 //   k_score   streams K once.  HBM-bound: d*e bytes read and 4 bytes written per token and KV head.
 #include "common.hpp"
+#include "kernels_core.hpp"
 
 namespace samkv {
 namespace {
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-
-// Sum over aligned groups of W lanes (W in {8, 16, 32}); every lane of a group ends with the total.
-// After the quad steps the mirrors pair lanes that already hold equal partial sums.
-template <int W>
-__device__ __forceinline__ float group_sum(float v) {
-  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
-  v += dpp_move<0x141>(v);  // row_half_mirror: lane i <-> 7 - i
-  if (W >= 16) v += dpp_move<0x140>(v);  // row_mirror: lane i <-> 15 - i
-  if (W >= 32) v += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // lane ^ 16
-  return v;
-}
-
-template <bool BF16>
-__device__ __forceinline__ void unpack16(const u32x4& x, float* f) {
-  if (BF16) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      f[2 * e] = bf16_lo(x[e]);
-      f[2 * e + 1] = bf16_hi(x[e]);
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(x[e]);
-  }
-}
 
 // Mean over `n_rows` rows of D channels starting at `src` (row-major, 16-byte loads); the result
 // lands in dst[0..D) (shared memory).  `red` is scratch of (256 / LPR) * D floats.  Fixed order.
@@ -298,59 +268,23 @@ __global__ __launch_bounds__(256) void k_score(PtrTable kt, IntTable cu_len, con
   // the document's vector for this KV head: qsrc is [N][heads][D]; `group` consecutive heads are averaged
   // (1 when the fold over the KV group has already been done, G when qsrc holds Eq. 1 per query head)
   float q[EPL];
-  {
-    const float* qp = qsrc + ((size_t)i * heads + (size_t)g * group) * D + sub * EPL;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) q[e] = 0.f;
-    for (int hh = 0; hh < group; ++hh)
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) q[e] += qp[hh * D + e];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) q[e] /= (float)group;
-  }
+  fold_query<EPL>(qsrc + ((size_t)i * heads + (size_t)g * group) * D + sub * EPL, D, group, q);
   const char* base = static_cast<const char*>(kt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
   float* out = scores + (size_t)g * total_len + cu_len.v[i];
-
-  u32x4 x[2][NB];
-#pragma unroll
-  for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      int row = row0 + (b2 * NB + b) * RPL + rg;
-      row = row < L ? row : L - 1;
-      x[b2][b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (size_t)row * ROW_BYTES));
-    }
-#pragma unroll
-  for (int b2 = 0; b2 < 2; ++b2) {
-    float keep = 0.f;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float f[EPL];
-      unpack16<BF16>(x[b2][b], f);
-      float s = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) s = fmaf(f[e], q[e], s);
-      s = group_sum<LPR>(s);
-      keep = (sub % NB == b) ? s : keep;
-    }
-    const int row = row0 + (b2 * NB + (sub % NB)) * RPL + rg;
-    if (sub < NB && row < L) out[row] = keep;
-  }
+  score_rows<BF16, D>(base, row0, L, q, [&](int row, float s) { out[row] = s; });
 }
 
+// Eq. 1 for every document; tells the caller where the vectors are and how many heads k_score must average.
 template <bool BF16, int D>
-hipError_t run(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s) {
+hipError_t run_prologue(const ScoreLaunch& a, hipStream_t s, QuerySrc* out) {
   const bool bias = a.q_loc != nullptr && a.n_ctx > 1;
-  constexpr int TILE = (64 / (D / (BF16 ? 8 : 4))) * 8 * 2 * 4;
-  dim3 gs((a.max_len + TILE - 1) / TILE, a.n_ctx, a.hkv);
   // bytes of Q rows that pass through one query head's workgroup in the one-launch prologue
   const size_t per_head = ((size_t)a.n_q_tok + (bias ? (size_t)a.n_ctx * a.w_loc : 0)) * D * (BF16 ? 2 : 4);
   if (a.n_ctx <= 64 && per_head <= (1u << 20)) {
     const size_t lds = (size_t)(2 * D + 16 * D + SAMKV_MAX_CTX + a.n_ctx * D) * sizeof(float);
     hipLaunchKernelGGL((k_prologue<BF16, D>), dim3(a.hq), dim3(1024), lds, s, a.q_tok, a.n_q_tok, a.q_loc, a.w_loc, a.n_ctx,
                        a.hq, bias ? 1 : 0, a.ws_loc);
-    hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_loc, a.hq, a.hq / a.hkv, a.scores,
-                       a.total_len);
+    out->q = a.ws_loc; out->heads = a.hq; out->group = a.hq / a.hkv;
     return hipGetLastError();
   }
   hipLaunchKernelGGL((k_pool<BF16, D>), dim3(a.hq, bias ? a.n_ctx + 1 : 1), dim3(256), 0, s, a.q_tok, a.n_q_tok,
@@ -359,15 +293,31 @@ hipError_t run(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, 
     hipLaunchKernelGGL(k_bias, dim3(a.hq), dim3(1024), 0, s, a.ws_que, a.ws_loc, a.ws_w, a.ws_base, a.n_ctx, a.hq, D);
   hipLaunchKernelGGL(k_qtilde, dim3(a.n_ctx, a.hkv), dim3(D), 0, s, a.ws_que, a.ws_base, a.ws_loc, a.ws_w, a.ws_qt,
                      a.n_ctx, a.hq, a.hkv, D, bias ? 1 : 0);
-  hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, a.ws_qt, a.hkv, 1, a.scores, a.total_len);
+  out->q = a.ws_qt; out->heads = a.hkv; out->group = 1;
+  return hipGetLastError();
+}
+
+template <bool BF16, int D>
+hipError_t run_keys(const ScoreLaunch& a, const QuerySrc& q, const PtrTable& k, const IntTable& cu_len, hipStream_t s) {
+  constexpr int TILE = (64 / (D / (BF16 ? 8 : 4))) * 8 * 2 * 4;
+  dim3 gs((a.max_len + TILE - 1) / TILE, a.n_ctx, a.hkv);
+  hipLaunchKernelGGL((k_score<BF16, D>), gs, dim3(256), 0, s, k, cu_len, q.q, q.heads, q.group, a.scores, a.total_len);
   return hipGetLastError();
 }
 
 }  // namespace
 
+hipError_t launch_score_prologue(const ScoreLaunch& a, hipStream_t s, QuerySrc* q) {
+  if (a.dtype == SAMKV_BF16) return a.d == 128 ? run_prologue<true, 128>(a, s, q) : run_prologue<true, 64>(a, s, q);
+  return a.d == 128 ? run_prologue<false, 128>(a, s, q) : run_prologue<false, 64>(a, s, q);
+}
+
 hipError_t launch_score(const ScoreLaunch& a, const PtrTable& k, const IntTable& cu_len, hipStream_t s) {
-  if (a.dtype == SAMKV_BF16) return a.d == 128 ? run<true, 128>(a, k, cu_len, s) : run<true, 64>(a, k, cu_len, s);
-  return a.d == 128 ? run<false, 128>(a, k, cu_len, s) : run<false, 64>(a, k, cu_len, s);
+  QuerySrc q;
+  hipError_t e = launch_score_prologue(a, s, &q);
+  if (e != hipSuccess) return e;
+  if (a.dtype == SAMKV_BF16) return a.d == 128 ? run_keys<true, 128>(a, q, k, cu_len, s) : run_keys<true, 64>(a, q, k, cu_len, s);
+  return a.d == 128 ? run_keys<false, 128>(a, q, k, cu_len, s) : run_keys<false, 64>(a, q, k, cu_len, s);
 }
 
 }  // namespace samkv

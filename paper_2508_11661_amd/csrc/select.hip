@@ -11,15 +11,10 @@
 //   3. kept = key > T, plus the first `need` positions with key == T (ties to the lower position);
 //      a block-wide exclusive scan of the per-thread counts gives every thread its output offset.
 #include "common.hpp"
+#include "kernels_core.hpp"
 
 namespace samkv {
 namespace {
-
-__device__ __forceinline__ uint32_t order_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u << 1) == 0u) u = 0u;  // -0 and +0 are one value: ties go by position, not by sign bit
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
 
 template <int E, int NT>
 __global__ __launch_bounds__(NT) void k_select(const float* scores, IntTable cu_len, IntTable cu_k, int total_len,
@@ -49,67 +44,8 @@ __global__ __launch_bounds__(NT) void k_select(const float* scores, IntTable cu_
 #pragma unroll
     for (int e = 0; e < E; ++e) key[e] = (p0 + e < L) ? order_key(row[p0 + e]) : 0u;
   }
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int p = p0 + e;
-    if (p < L && (p < n_sink || p >= L - n_local)) key[e] = 0xFFFFFFFFu;
-  }
-
-  // ---- k-th largest key, bit by bit ------------------------------------------------------------
-  uint32_t prefix = 0;
-  uint32_t kk = (uint32_t)k;
-  for (int b = 31; b >= 0; --b) {
-    // candidate: agrees with the decided bits above b and has bit b set (padding keys are 0: never)
-    const uint32_t want = (prefix >> b) | 1u;
-    uint32_t c = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) c += __popcll(__ballot((key[e] >> b) == want));
-    if (lane == 0) cnt[b & 1][wave] = c;
-    __syncthreads();
-    uint32_t tot = 0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) tot += cnt[b & 1][w];
-    if (tot >= kk) prefix |= (1u << b); else kk -= tot;
-  }
-  const uint32_t T = prefix;
-  const uint32_t need = kk;  // how many positions with key == T are kept
-
-  // ---- ordered compaction ------------------------------------------------------------------------
-  uint32_t n_gt = 0, n_eq = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const bool ok = p0 + e < L;
-    n_gt += (ok && key[e] > T) ? 1u : 0u;
-    n_eq += (ok && key[e] == T) ? 1u : 0u;
-  }
-  // both counts can reach 65536 (a full-length row of equal keys kept whole): 32 bits each
-  uint64_t packed = (uint64_t)n_gt | ((uint64_t)n_eq << 32);
-  uint64_t incl = packed;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    uint64_t o = __shfl_up(incl, off);
-    if (lane >= off) incl += o;
-  }
-  if (lane == 63) wsum[wave] = incl;
-  __syncthreads();
-  uint64_t base = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) base += (w < wave) ? wsum[w] : 0ull;
-  const uint64_t excl = base + incl - packed;
-  uint32_t gt_before = (uint32_t)excl, eq_before = (uint32_t)(excl >> 32);
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    if (p0 + e < L) {
-      const bool is_eq = key[e] == T;
-      const bool take = key[e] > T || (is_eq && eq_before < need);
-      if (take) {
-        const uint32_t pos = gt_before + (eq_before < need ? eq_before : need);
-        out[pos] = p0 + e;
-      }
-      gt_before += key[e] > T ? 1u : 0u;
-      eq_before += is_eq ? 1u : 0u;
-    }
-  }
+  force_keys<E>(key, p0, L, n_sink, n_local);
+  select_from_keys<E, NT>(key, p0, L, k, out, cnt, wsum);
 }
 
 template <int E, int NT>

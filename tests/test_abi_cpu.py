@@ -109,6 +109,12 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_score(ctypes.byref(_caches(S, lens=(8, 0))), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
     assert L.samkv_score(ctypes.byref(_caches(S, lens=(8, 70000))), fake, 4, None, 0, fake, fake, 1 << 20, None) == -2
     assert L.samkv_score(ctypes.byref(_caches(S, k=False)), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    # samkv_score_select
+    assert L.samkv_score_select(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, None, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_score_select(ctypes.byref(ok), fake, 4, None, 0, 0.0, 0, 0, fake, fake, None, cu, fake, 1 << 20, None) == -1
+    assert L.samkv_score_select(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu, None, 0, None) == -3
+    assert L.samkv_score_select(ctypes.byref(_caches(S, lens=(8, 9000))), fake, 4, None, 0, 0.5, 0, 0, None, fake, None, cu,
+                                fake, 1 << 20, None) == -1   # rows beyond the fused kernel need the score buffer
     # samkv_topk_select
     assert L.samkv_topk_select(None, ctypes.byref(ok), 0.5, 0, 0, fake, None, cu, None, 0, None) == -1
     assert L.samkv_topk_select(fake, ctypes.byref(ok), 0.0, 0, 0, fake, None, cu, None, 0, None) == -1

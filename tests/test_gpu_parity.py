@@ -448,3 +448,38 @@ def test_gather_by_global_positions_other_row_sizes(S, dtype, d):
     S.samkv_gather_g(caches, torch.from_numpy(gidx).cuda(), k_c, v_c)
     assert np.array_equal(k_c.float().cpu().numpy(), O.gather_global(x.k, gidx))
     assert np.array_equal(v_c.float().cpu().numpy(), O.gather_global(x.v, gidx))
+
+
+@pytest.mark.parametrize("dtype,d,lens,ratio,n_sink,n_local", [
+    ("bf16", 128, [300, 77, 1025, 513], 0.3, 4, 8), ("bf16", 64, [1000, 1024, 5], 0.15, 0, 0),
+    ("f32", 128, [4096, 4097, 130], 0.1, 2, 2), ("f32", 64, [8192, 63, 2500], 0.2, 0, 8),
+    ("bf16", 128, [9000, 700], 0.05, 1, 1),        # longer than the fused kernel's rows: falls back to two launches
+])
+def test_fused_score_select_equals_the_two_calls(S, dtype, d, lens, ratio, n_sink, n_local):
+    """One pass over K must keep exactly what samkv_score followed by samkv_topk_select keeps (bit-identical scores
+    and positions), and that must agree with the oracle under the tie-margin rule."""
+    import torch
+    x = synth.make_small(81, dtype, lens, 8, 2, d, 6, 9)
+    ref = H.oracle_front(x, ratio, n_sink, n_local)
+    caches = H.upload_caches(x)
+    q_tok, q_loc = H.to_dev(x.q_tok, dtype), H.to_dev(x.q_loc, dtype)
+    m = int(ref.cu_k[-1])
+    ws = _ws(S, x, x.workload.n_q_tok, m)
+    sc_a = torch.full((2, caches.total_len), float("nan"), device="cuda")
+    idx_a = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+    S.samkv_score(caches, q_tok, q_loc, sc_a, ws)
+    cu_a = S.samkv_topk_select(sc_a, caches, ratio, n_sink, n_local, idx_a, None, ws)
+    sc_b = torch.full((2, caches.total_len), float("nan"), device="cuda")
+    idx_b = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+    cu_dev = torch.zeros((len(lens) + 1,), dtype=torch.int32, device="cuda")
+    cu_b = S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, sc_b, idx_b, cu_dev, ws)
+    assert cu_a == cu_b == ref.cu_k.tolist() == cu_dev.cpu().tolist()
+    assert torch.equal(sc_a, sc_b) and torch.equal(idx_a, idx_b)
+    H.compare_kept_sets(idx_b.cpu().numpy(), ref, n_sink, n_local)
+    if max(lens) <= 8192:                           # without a score buffer
+        idx_c = torch.full((2, m), -1, dtype=torch.int32, device="cuda")
+        S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, None, idx_c, None, ws)
+        assert torch.equal(idx_a, idx_c)
+    else:
+        with pytest.raises(S.SamKVError):
+            S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, None, idx_b, None, ws)
