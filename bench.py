@@ -114,6 +114,39 @@ def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
             "sample": sample, "seconds_measured": round(wall, 2), "ms_per_step_extrapolated": round(total * 1e3, 1)}
 
 
+def measured_peaks(samkv, iters=7):
+    """What this device sustains on a pure-MFMA loop (the bf16 32x32x16 product, 2 and 4 waves per SIMD) and on a
+    plain 1 GiB streaming copy: the ceilings a kernel's rate can be read against besides the published peaks."""
+    import torch
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            work = fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return work, sorted(ts)[iters // 2]
+
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    out = {}
+    for wps in (2, 4):                       # waves per SIMD: a workgroup is 4 waves, one per SIMD
+        flop, ms = timed(lambda: samkv.samkv_peak_mfma_bf16(sink, n_cu * wps, 4000 // wps))
+        out[f"mfma_bf16_tflops_{wps}_waves_per_simd"] = round(flop / ms / 1e9, 1)
+    out["mfma_bf16_tflops"] = max(v for k, v in out.items() if k.startswith("mfma"))
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    nbytes, ms = timed(lambda: samkv.samkv_peak_copy(src, dst))
+    out["copy_gbs_read_plus_write"] = round(nbytes / ms / 1e6, 1)
+    out["compute_units"] = n_cu
+    return out
+
+
 def at_scale(samkv, iters=5):
     """Kernel timings at the shapes of the largest workload (64 documents x 4096 tokens, 64/8 heads, d = 128,
     256 query tokens, 15 % budget), where the kernels are bandwidth- or MFMA-bound instead of latency-bound.
@@ -229,6 +262,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     ap.add_argument("--no-at-scale", action="store_true",
                     help="skip the extra kernel timings at the shapes of the large-cache workload")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the pure-MFMA and plain-copy micro-kernels")
     ap.add_argument("--no-graph", dest="graph", action="store_false",
                     help="skip the extra timing of the same steps as HIP graph replays")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -401,6 +435,13 @@ def main() -> int:
         "per_kernel": per_kernel,
         "roofline": roof,
     }
+    if not args.no_peaks:
+        mp = measured_peaks(samkv)
+        out["measured_peaks"] = mp
+        if roof["bound"] == "mfma":
+            roof["frac_of_measured_peak"] = round(roof["achieved"] / mp["mfma_bf16_tflops"], 4)
+        elif roof["bound"] == "hbm":
+            roof["frac_of_measured_peak"] = round(roof["achieved"] / mp["copy_gbs_read_plus_write"], 4)
     if graph_ms is not None:
         out["hip_graph"] = {"ms_per_step": round(graph_ms, 4), "value": round(sum(w.lens) * n_layers / (graph_ms * 1e-3), 1),
                             "unit": "tokens/s", "note": "the same steps launched as replays of captured HIP graphs"}

@@ -276,6 +276,15 @@ enum { SAMKV_OVERWRITE = 0, SAMKV_FUSION = 1 };
 int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, int32_t m_total,
                     int32_t n_kv_heads, int32_t head_dim, int32_t dtype, int32_t mode, void* stream);
 
+/* Diagnostics, not part of the method: two micro-kernels with which a benchmark measures what this device
+ * sustains, to quote kernel rates against the measured ceiling as well as the published one.  The caller times the
+ * launch (HIP events on `stream`).
+ *   samkv_peak_mfma_bf16  n_blocks workgroups of 4 waves, each wave issues iters * 16 independent
+ *                         v_mfma_f32_32x32x16_bf16: n_blocks * 4 * iters * 16 * 32768 flop.  sink: 4 bytes, untouched.
+ *   samkv_peak_copy       dst[0..bytes) = src[0..bytes), 16-byte aligned, bytes a multiple of 16. */
+int samkv_peak_mfma_bf16(float* sink, int32_t n_blocks, int32_t iters, void* stream);
+int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,72 @@
+// Two micro-kernels that measure what THIS device sustains, so that the benchmark can quote a kernel's rate
+// against the measured ceiling as well as against the published one:
+//   k_peak_mfma   nothing but independent v_mfma_f32_32x32x16_bf16 instructions (the product the attention kernels
+//                 are built on), four accumulators per wave so that the matrix pipe never waits on a result
+//   k_peak_copy   a plain streaming copy, 16 bytes per lane, non-temporal
+// Neither is part of the method; the benchmark times the launches with HIP events.
+#include "common.hpp"
+
+namespace samkv {
+namespace {
+
+__global__ __launch_bounds__(256) void k_peak_mfma(float* sink, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+    b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += acc[i][j];
+  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; never true for these operands
+}
+
+__global__ __launch_bounds__(256) void k_peak_copy(const u32x4* src, u32x4* dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256 * 4;
+  for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
+    u32x4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + (size_t)u * 256;
+      x[u] = __builtin_nontemporal_load(src + (j < n16 ? j : n16 - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + (size_t)u * 256;
+      if (j < n16) __builtin_nontemporal_store(x[u], dst + j);
+    }
+  }
+}
+
+}  // namespace
+
+// flop of one launch: n_blocks * 4 waves * iters * 16 instructions * 32768
+hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, hipStream_t s) {
+  hipLaunchKernelGGL(k_peak_mfma, dim3(n_blocks), dim3(256), 0, s, sink, iters);
+  return hipGetLastError();
+}
+
+hipError_t launch_peak_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  size_t blocks = (n16 + 1023) / 1024;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(k_peak_copy, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const u32x4*>(src),
+                     static_cast<u32x4*>(dst), n16);
+  return hipGetLastError();
+}
+
+}  // namespace samkv

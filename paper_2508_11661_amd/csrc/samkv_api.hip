@@ -584,6 +584,18 @@ int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, con
   return gather_q_common(caches, s, cu_k, q_cache, idx, q_rec, stream);
 }
 
+int samkv_peak_mfma_bf16(float* sink, int32_t n_blocks, int32_t iters, void* stream) {
+  if (sink == nullptr || n_blocks < 1 || n_blocks > (1 << 20) || iters < 1) return SAMKV_EINVAL;
+  return dev(launch_peak_mfma(sink, n_blocks, iters, static_cast<hipStream_t>(stream)));
+}
+
+int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (src == nullptr || dst == nullptr || bytes < 16 || bytes % 16 != 0 || ((uintptr_t)src % 16) != 0 ||
+      ((uintptr_t)dst % 16) != 0)
+    return SAMKV_EINVAL;
+  return dev(launch_peak_copy(src, dst, bytes, static_cast<hipStream_t>(stream)));
+}
+
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
                          void* ws, size_t ws_bytes, void* stream) {

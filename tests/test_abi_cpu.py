@@ -26,7 +26,7 @@ def S():
 def test_library_exports_every_declared_symbol(S):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(samkv_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(samkv_[a-z0-9_]+)\s*\(", text))
     assert declared == set(S.EXPORTS)
     for name in declared:
         assert hasattr(S._lib, name), name
