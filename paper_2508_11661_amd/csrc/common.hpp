@@ -94,8 +94,11 @@ hipError_t launch_gather_q(const GatherLaunch& a, const PtrTable& q, const IntTa
 // Waves per workgroup of the bf16 attention kernel (each wave owns 32 query rows).  Eight waves share
 // one K/V tile stream between twice as many rows; that pays once there are enough row tiles to keep
 // every compute unit busy, otherwise four waves give more workgroups to spread.
+#ifndef SAMKV_WAVE8_MIN_TILES
+#define SAMKV_WAVE8_MIN_TILES 384  // causal: number of 256-row tiles (1.5 per compute unit) from which eight waves pay; measured
+#endif
 inline int attn_bf16_waves(int causal, int n_batch, int rows) {
-  if (causal) return (long long)n_batch * ((rows + 255) / 256) >= 1024 ? 8 : 4;
+  if (causal) return (long long)n_batch * ((rows + 255) / 256) >= SAMKV_WAVE8_MIN_TILES ? 8 : 4;
   return rows >= 1024 ? 8 : 4;
 }
 
