@@ -57,15 +57,16 @@ def algorithmic_work(w, lens, m, n_q_tok):
 def read_traffic(workload, kernel: str):
     """HBM bytes per launch (read + write) of a kernel, from the committed rocprofv3 --pmc summary of this
     workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
-    prefix = {"score": "k_score<", "select": "k_select", "gather": "k_gather", "score_select": "k_score_select",
-              "recompute_attn": "k_attn_%s<%d, true" % (workload.dtype, workload.head_dim),
-              "query_attn": "k_attn_%s<%d, false" % (workload.dtype, workload.head_dim)}[kernel]
+    prefixes = {"score": ["k_score<"], "select": ["k_select"], "gather": ["k_gather<"], "score_select": ["k_score_select"],
+                "recompute_attn": ["k_attn_%s<%d, true" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<true" % workload.dtype],
+                "query_attn": ["k_attn_%s<%d, false" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<false" % workload.dtype],
+                }[kernel]
     try:
         lines = open(os.path.join(ROOT, "profiles", f"bench_{workload.name}.txt")).read().splitlines()
     except OSError:
         return None
     for line in lines:
-        if line.startswith(prefix):
+        if any(line.startswith(p) for p in prefixes):
             try:
                 rd, wr = float(line.split()[-2]), float(line.split()[-1])
                 return (rd + wr) * 1e6
