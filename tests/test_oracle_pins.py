@@ -458,7 +458,7 @@ def test_generated_recomputed_rows_have_cosine_near_the_reported_value():
     old = np.concatenate(x.k, axis=1)[:, :500]
     new = synth.make_recomputed_rows(x.workload, 0, old, x.sigma_k, 0)
     cos = np.einsum("gmc,gmc->gm", new, old) / (np.linalg.norm(new, axis=2) * np.linalg.norm(old, axis=2))
-    assert 0.85 < np.median(cos) < 0.95     # Sec. 3.3: the fusion weight is "around 0.9"
+    assert 0.85 < np.median(cos) < 0.95     # Sec. 3.3 reports a fusion weight of roughly 0.9
 
 
 # ------------------------------------------------------------------ query prefill with its own K/V
