@@ -66,6 +66,14 @@ def _full_size(name, layer, ratio, n_rows_rec, n_rows_q):
     got_o = buf.q_out[heads][:, torch.from_numpy(q_rows).cuda()].cpu().numpy()
     got_l = buf.q_lse[heads][:, torch.from_numpy(q_rows).cuda()].cpu().numpy()
     e_q = H.check_attention(got_o, got_l, o_ref, l_ref, w.dtype, f"{name} query")
+    # the selection exactly as bench.py launches it (no score buffer), and the two separate calls: same bits
+    idx2 = torch.full_like(buf.idx, -1)
+    S.samkv_score_select(caches, q_tok, q_loc, ratio, 0, 0, None, idx2, None, buf.ws)
+    assert torch.equal(idx2, buf.idx)
+    sc3, idx3 = torch.empty_like(buf.scores), torch.full_like(buf.idx, -1)
+    S.samkv_score(caches, q_tok, q_loc, sc3, buf.ws)
+    S.samkv_topk_select(sc3, caches, ratio, 0, 0, idx3, None, buf.ws)
+    assert torch.equal(sc3, buf.scores) and torch.equal(idx3, buf.idx)
     print(f"{name} layer {layer} ratio {ratio}: M={m}, rows differing inside the tie margin={in_margin}, "
           f"KV heads exact={len(clean)}/{w.n_kv_heads}, max |err| recompute={e_rec:.2e} query={e_q:.2e}")
     return m
