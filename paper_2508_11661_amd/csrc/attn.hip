@@ -35,6 +35,18 @@ struct AttnArgs {
   float scale;
 };
 
+// Exchange between lane l and lane l ^ 32 on the vector ALU (v_permlane32_swap; with both operands equal the first
+// result holds the lower half's values in both halves and the second the upper half's): no trip through LDS as a
+// 64-wide shuffle would take, which matters because the row maximum sits at the head of every step's dependence chain.
+__device__ __forceinline__ float max_across_halves(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -196,7 +208,7 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][j]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = max_across_halves(mx);
       const float m_new = fmaxf(m_run, mx * c2);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
@@ -276,7 +288,7 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
     m_run = m_new;
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = sum_across_halves(l_run);
   const float inv = 1.f / l_tot;
   if (r < a.rows) {
     const size_t row_id = (size_t)batch * a.rows + r;
@@ -452,15 +464,34 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[kb][j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_across_halves(mx);
     return mx * c2;
   };
   auto kfrags = [&](const char* ks, int kb, bf16x8 (&ak)[ND]) {
 #pragma unroll
     for (int dc = 0; dc < ND; ++dc) ak[dc] = *reinterpret_cast<const bf16x8*>(ks + kaddr[dc] + kb * 32 * 256);
   };
+  // V^T fragments of key group g (16 keys) for the NV blocks of O^T: two transposing reads each
+  auto vfrags = [&](const char* vs, int g, bf16x8 (&av)[NV]) {
+#pragma unroll
+    for (int dvb = 0; dvb < NV; ++dvb) {
+      const char* vp = vs + vaddr[dvb] + g * 16 * 256;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * 256));
+      union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
+      u.s.lo = lo;
+      u.s.hi = hi;
+      av[dvb] = u.v;
+    }
+  };
+  // LDS reads may not be moved across this point (everything else may): keeps a fragment load where it was written,
+  // i.e. one group of products ahead of its use, instead of right in front of it
+  constexpr int kHoldLds = 0x47F;
   auto weights_pv = [&](f32x16 (&s)[2], const char* vs, float m_use) {
     bf16x8 bp[2][2];
+    bf16x8 va[2][NV];
+    vfrags(vs, 0, va[0]);  // lands while the weights are computed
+    __builtin_amdgcn_sched_barrier(kHoldLds);
     float psum = 0.f;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
@@ -478,19 +509,15 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
         }
     l_run += psum;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int g = 0; g < 4; ++g) {
+      if (g + 1 < 4) {
+        vfrags(vs, g + 1, va[(g + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(kHoldLds);
+      }
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int dvb = 0; dvb < NV; ++dvb) {
-          const char* vp = vs + vaddr[dvb] + (kb * 32 + s2 * 16) * 256;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * 256));
-          union { struct { s16x4 lo, hi; } s; bf16x8 v; } av;
-          av.s.lo = lo;
-          av.s.hi = hi;
-          o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
-        }
+      for (int dvb = 0; dvb < NV; ++dvb)
+        o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[g & 1][dvb], bp[g >> 1][g & 1], o[dvb], 0, 0, 0);
+    }
   };
 
   // ---- prologue: K(0), V(0), K(1) must have landed; V(1), K(2) stay in flight
@@ -559,7 +586,7 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
     if (tile + 1 < n_tiles) step(tile + 1, sB, sA);
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = sum_across_halves(l_run);
   const float inv = 1.f / l_tot;
   if (r < a.rows) {
     const size_t row_id = (size_t)batch * a.rows + r;
