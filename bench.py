@@ -263,6 +263,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     ap.add_argument("--no-at-scale", action="store_true",
                     help="skip the extra kernel timings at the shapes of the large-cache workload")
+    ap.add_argument("--streams", type=int, default=None,
+                    help="HIP streams the layers of a step are spread over (default 1 for one layer, else 2)")
     ap.add_argument("--no-peaks", action="store_true", help="skip the pure-MFMA and plain-copy micro-kernels")
     ap.add_argument("--no-graph", dest="graph", action="store_false",
                     help="skip the extra timing of the same steps as HIP graph replays")
@@ -301,18 +303,22 @@ def main() -> int:
             sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads), q_tok=to_dev(x.q_tok, w.dtype),
                              q_loc=to_dev(x.q_loc, w.dtype),
                              q_rec=to_dev(synth.make_q_rec(w, l, m), w.dtype)))
-    buf = samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio)
+    # The layers of a multi-layer workload are independent (per-layer caches, stored Q states as inputs), so they are
+    # spread over `n_streams` HIP streams of default priority, each with its own buffers: the tail of one layer's
+    # causal attention (a few long row tiles) overlaps with the next layer's first kernels.
+    n_streams = args.streams or (1 if n_layers == 1 else 2)
+    bufs = [samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio) for _ in range(n_streams)]
+    streams = [torch.cuda.current_stream()] if n_streams == 1 else [torch.cuda.Stream() for _ in range(n_streams)]
     torch.cuda.synchronize()
 
     calls = {
-        "score": lambda s: samkv.samkv_score(s["caches"], s["q_tok"], s["q_loc"], buf.scores, buf.ws),
-        "select": lambda s: samkv.samkv_topk_select(buf.scores, s["caches"], ratio, 0, 0, buf.idx, buf.cu_k_dev, buf.ws),
-        "gather": lambda s: samkv.samkv_gather(s["caches"], buf.idx, ratio, buf.k_c, buf.v_c),
-        "recompute_attn": lambda s: samkv.samkv_recompute_attn(s["q_rec"], buf.k_c, buf.v_c, scale, buf.rec_out,
-                                                               buf.rec_lse, buf.ws),
-        "query_attn": lambda s: samkv.samkv_query_attn(s["q_tok"], buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws),
-        "score_select": lambda s: samkv.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, buf.idx,
-                                                           buf.cu_k_dev, buf.ws),
+        "score": lambda s, b: samkv.samkv_score(s["caches"], s["q_tok"], s["q_loc"], b.scores, b.ws),
+        "select": lambda s, b: samkv.samkv_topk_select(b.scores, s["caches"], ratio, 0, 0, b.idx, b.cu_k_dev, b.ws),
+        "gather": lambda s, b: samkv.samkv_gather(s["caches"], b.idx, ratio, b.k_c, b.v_c),
+        "recompute_attn": lambda s, b: samkv.samkv_recompute_attn(s["q_rec"], b.k_c, b.v_c, scale, b.rec_out, b.rec_lse, b.ws),
+        "query_attn": lambda s, b: samkv.samkv_query_attn(s["q_tok"], b.k_c, b.v_c, scale, b.q_out, b.q_lse, b.ws),
+        "score_select": lambda s, b: samkv.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, b.idx,
+                                                              b.cu_k_dev, b.ws),
     }
 
     def step(i, events=None, only=None, names=STEP):
@@ -320,15 +326,17 @@ def main() -> int:
         recorded around every call, or only around the call named `only`."""
         for l in range(n_layers):
             s = sets[(i * n_layers + l) % len(sets)]
-            for name in names:
-                if events is not None and (only is None or only == name):
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    calls[name](s)
-                    b.record()
-                    events[name].append((a, b))
-                else:
-                    calls[name](s)
+            b = bufs[l % n_streams]
+            with torch.cuda.stream(streams[l % n_streams]):
+                for name in names:
+                    if events is not None and (only is None or only == name):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        calls[name](s, b)
+                        e1.record()
+                        events[name].append((e0, e1))
+                    else:
+                        calls[name](s, b)
 
     def mean_ms(evs):
         return float(np.mean([a.elapsed_time(b) for a, b in evs]))
@@ -363,9 +371,10 @@ def main() -> int:
     # the same K steps as replays of captured HIP graphs (one graph per rotated input set): what a serving loop
     # would launch.  Reported beside the eager figure, not instead of it.
     graph_ms = None
-    if args.graph and len(sets) <= 64:
+    if args.graph and len(sets) <= 64 and n_streams == 1:
         side = torch.cuda.Stream()
         graphs = []
+        streams[0] = side                  # step() launches on streams[0]: capture on the side stream
         with torch.cuda.stream(side):
             for gi in range(len(sets) // n_layers):
                 g = torch.cuda.CUDAGraph()
@@ -432,7 +441,7 @@ def main() -> int:
         "config": {"workload": w.name, "n_layers": n_layers, "n_ctx": w.n_ctx, "ctx_len": w.ctx_len,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_q_tok": w.n_q_tok, "budget_ratio": ratio, "kept_per_ctx": m // w.n_ctx, "m_total": m,
-                   "input_copies_rotated": n_rot},
+                   "input_copies_rotated": n_rot, "streams": n_streams},
         "per_kernel": per_kernel,
         "roofline": roof,
     }
