@@ -14,6 +14,18 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
+def paper_constants():
+    """tests/golden/paper_constants.txt: the few numbers the paper prints, each with the place it prints it."""
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_constants.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = (x.strip() for x in line.split("="))
+            out[k] = float(v)
+    return out
+
+
 # ------------------------------------------------------------------ Eq. 1 (personalized query)
 def test_pooled_query_hand_values():
     # two tokens (1,2) and (3,6) -> mean (2,4)   [Sec. 3.1: mean pooling over the sequence dimension]
@@ -115,12 +127,13 @@ def test_eq1_zero_norm_local_query_gets_zero_weight():
 
 
 def test_generated_local_queries_have_small_cosine():
-    # Sec. 3.1 reports cos(Q_que, Q_loc) "typically" within +-0.3; the synthetic caches land there
+    # Sec. 3.1 reports the range cos(Q_que, Q_loc) usually stays in; the synthetic caches land there
+    bound = paper_constants()["cos_query_local_max"]
     x = synth.make_layer(synth.WORKLOADS["llama3_8b_layer"])
     que = O.pooled_query(x.q_tok)
     loc = O.local_query(x.q_loc)
     cos = [O.abs_cos(que[h], loc[j, h]) for j in range(loc.shape[0]) for h in range(que.shape[0])]
-    assert np.median(cos) < 0.3 and np.quantile(cos, 0.9) < 0.45
+    assert np.median(cos) < bound and np.quantile(cos, 0.9) < 1.5 * bound
 
 
 # ------------------------------------------------------------------ scoring
@@ -458,7 +471,7 @@ def test_generated_recomputed_rows_have_cosine_near_the_reported_value():
     old = np.concatenate(x.k, axis=1)[:, :500]
     new = synth.make_recomputed_rows(x.workload, 0, old, x.sigma_k, 0)
     cos = np.einsum("gmc,gmc->gm", new, old) / (np.linalg.norm(new, axis=2) * np.linalg.norm(old, axis=2))
-    assert 0.85 < np.median(cos) < 0.95     # Sec. 3.3 reports a fusion weight of roughly 0.9
+    assert abs(np.median(cos) - paper_constants()["fusion_cos_typical"]) < 0.05     # the fusion weight Sec. 3.3 reports
 
 
 # ------------------------------------------------------------------ query prefill with its own K/V
@@ -625,3 +638,20 @@ def test_gather_global_matches_per_document_gather():
     assert np.array_equal(O.gather_global(k, gidx), k_c) and np.array_equal(O.gather_global(v, gidx), v_c)
     q = [r.standard_normal((6, L, 4)) for L in lens]
     assert np.array_equal(O.gather_global(q, gidx, group=3), O.gather_q(q, idx, cu))
+
+
+# ------------------------------------------------------------------ the constants the paper prints
+def test_paper_constants_meet_oracle_defaults_and_workloads():
+    c = paper_constants()
+    # Setup: 64-token blocks, 1 initial and 2 local blocks always kept -> the oracle's defaults force exactly those
+    block, ni, nl = int(c["block_size"]), int(c["initial_blocks"]), int(c["local_blocks"])
+    L = 20 * block + 7                                   # 21 blocks, the last one 7 tokens long
+    idx, cu = O.block_select([np.zeros((1, 21))], [L], block, [0.0])
+    assert cu.tolist() == [0, ni * block + (nl - 1) * block + 7]
+    assert idx[0].tolist() == list(range(block)) + list(range(19 * block, L))
+    # Table 1: the budget of the named workloads (15 %) is the paper's sequence ratio to within a point, and every
+    # kept token is recomputed, which is what its recomputation ratio says to within a point
+    for w in synth.WORKLOADS.values():
+        if 0.15 in w.ratios:
+            kept = sum(O.kept_count(n, 0.15) for n in w.lens) / sum(w.lens) * 100
+            assert abs(kept - c["sequence_ratio_percent"]) < 1.0 and abs(kept - c["recompute_ratio_percent"]) < 1.0
