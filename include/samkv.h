@@ -30,6 +30,9 @@
  *   - Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - Return value: SAMKV_OK or a negative error.  Argument errors are found before anything is
  *     launched and leave the outputs untouched.  Results are deterministic (no float atomics).
+ *   - HIP graphs: every call only enqueues kernels (no memsets, no copies, no allocation), so a sequence of calls
+ *     can be captured.  The first attention call of a process raises the dynamic-LDS limit of its kernel with
+ *     hipFuncSetAttribute; make one call of each attention entry point before capturing.
  *   - Limits: head_dim in {64, 128}; n_ctx <= SAMKV_MAX_CTX; each document at most SAMKV_MAX_LEN
  *     tokens; n_q_heads a multiple of n_kv_heads.
  */
