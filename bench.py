@@ -263,6 +263,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     ap.add_argument("--no-at-scale", action="store_true",
                     help="skip the extra kernel timings at the shapes of the large-cache workload")
+    ap.add_argument("--layout", choices=("stacked", "per-layer"), default="stacked",
+                    help="multi-layer workloads: all layers in one tensor per document and one call per entry point, "
+                         "or one set of calls per layer")
     ap.add_argument("--streams", type=int, default=None,
                     help="HIP streams the layers of a step are spread over (default 1 for one layer, else 2)")
     ap.add_argument("--no-peaks", action="store_true", help="skip the pure-MFMA and plain-copy micro-kernels")
@@ -295,18 +298,33 @@ def main() -> int:
     m = sum(samkv.samkv_kept_count(n, ratio) for n in w.lens)
     kv_bytes = 2 * sum(w.lens) * w.n_kv_heads * w.head_dim * e * n_layers
     n_rot = max(1, min(16, math.ceil(512e6 / kv_bytes)))
+    # Layout of a multi-layer workload.  "stacked": every document's cache holds all layers, [(layer, KV head)][L][d],
+    # and so do the Q tensors; the library knows nothing about layers (a head is a head, query head h reads KV head
+    # h / G, which stays inside its layer), so ONE call per entry point serves all layers: 4 launches of full-chip
+    # size per step instead of 4 small ones per layer.  "per-layer": one set of calls per layer.
+    stacked = n_layers > 1 and args.layout == "stacked"
+    layers_per_call = n_layers if stacked else 1
     sets = []
     for rot in range(n_rot):
+        if stacked:
+            cat = lambda arrs, axis=0: to_dev(np.concatenate(arrs, axis=axis), w.dtype)
+            k = [cat([x.k[i] for x in layers_np]) for i in range(w.n_ctx)]
+            v = [cat([x.v[i] for x in layers_np]) for i in range(w.n_ctx)]
+            sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads * n_layers), q_tok=cat([x.q_tok for x in layers_np]),
+                             q_loc=cat([x.q_loc for x in layers_np], axis=1),
+                             q_rec=cat([synth.make_q_rec(w, l, m) for l in range(n_layers)])))
+            continue
         for l, x in enumerate(layers_np):
             k = [to_dev(a, w.dtype) for a in x.k]
             v = [to_dev(a, w.dtype) for a in x.v]
             sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads), q_tok=to_dev(x.q_tok, w.dtype),
                              q_loc=to_dev(x.q_loc, w.dtype),
                              q_rec=to_dev(synth.make_q_rec(w, l, m), w.dtype)))
+    calls_per_step = 1 if stacked else n_layers
     # The layers of a multi-layer workload are independent (per-layer caches, stored Q states as inputs), so they are
     # spread over `n_streams` HIP streams of default priority, each with its own buffers: the tail of one layer's
     # causal attention (a few long row tiles) overlaps with the next layer's first kernels.
-    n_streams = args.streams or (1 if n_layers == 1 else 2)
+    n_streams = args.streams or (1 if calls_per_step == 1 else 2)
     bufs = [samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio) for _ in range(n_streams)]
     streams = [torch.cuda.current_stream()] if n_streams == 1 else [torch.cuda.Stream() for _ in range(n_streams)]
     torch.cuda.synchronize()
@@ -324,8 +342,8 @@ def main() -> int:
     def step(i, events=None, only=None, names=STEP):
         """One pass of the hot path.  `events`: dict name -> list of (start, end) HIP events on the launch stream,
         recorded around every call, or only around the call named `only`."""
-        for l in range(n_layers):
-            s = sets[(i * n_layers + l) % len(sets)]
+        for l in range(calls_per_step):
+            s = sets[(i * calls_per_step + l) % len(sets)]
             b = bufs[l % n_streams]
             with torch.cuda.stream(streams[l % n_streams]):
                 for name in names:
@@ -376,7 +394,7 @@ def main() -> int:
         graphs = []
         streams[0] = side                  # step() launches on streams[0]: capture on the side stream
         with torch.cuda.stream(side):
-            for gi in range(len(sets) // n_layers):
+            for gi in range(len(sets) // calls_per_step):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=side):
                     step(gi)
@@ -402,8 +420,8 @@ def main() -> int:
     per_kernel = {}
     for name in STEP + tuple(n for n in KERNELS if n not in STEP):
         ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
-        gbs = work[name]["bytes"] / (ms * 1e-3) / 1e9
-        tfl = work[name]["flops"] / (ms * 1e-3) / 1e12
+        gbs = work[name]["bytes"] * layers_per_call / (ms * 1e-3) / 1e9
+        tfl = work[name]["flops"] * layers_per_call / (ms * 1e-3) / 1e12
         per_kernel[name] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
                             "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
         if name.endswith("attn"):
@@ -411,7 +429,7 @@ def main() -> int:
             per_kernel[name]["frac_compute"] = round(tfl / peak, 4)
 
     ss_ms = per_kernel["score"]["ms"] + per_kernel["select"]["ms"]
-    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) / (ss_ms * 1e-3) / 1e9
+    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) * layers_per_call / (ss_ms * 1e-3) / 1e9
     per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
                                   "note": "the two separate calls as one K-streaming stage, for comparison with the "
                                           "fused score_select call that the timed step launches"}
@@ -426,7 +444,7 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(per_kernel[dom]["GB/s"] / HBM_PEAK_GBS, 4)}
     roof["avg_launch_ms"] = per_kernel[dom]["ms"]
     roof["traffic"] = read_traffic(w, dom)
-    roof["algorithmic"] = work[dom]["flops"] if roof["bound"] != "hbm" else work[dom]["bytes"]
+    roof["algorithmic"] = (work[dom]["flops"] if roof["bound"] != "hbm" else work[dom]["bytes"]) * layers_per_call
 
     out = {
         "metric": "KV tokens scored per second through the whole sparse-prefill hot path "
@@ -441,7 +459,8 @@ def main() -> int:
         "config": {"workload": w.name, "n_layers": n_layers, "n_ctx": w.n_ctx, "ctx_len": w.ctx_len,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_q_tok": w.n_q_tok, "budget_ratio": ratio, "kept_per_ctx": m // w.n_ctx, "m_total": m,
-                   "input_copies_rotated": n_rot, "streams": n_streams},
+                   "input_copies_rotated": n_rot, "streams": n_streams,
+                   "layout": "stacked: one call per entry point serves all layers" if stacked else "per-layer calls"},
         "per_kernel": per_kernel,
         "roofline": roof,
     }

@@ -32,6 +32,7 @@ struct AttnArgs {
   float* part_o;
   float* part_lse;
   int rows, m, batch_per_kv, n_batch, n_split, chunk;
+  int kv_groups;  // > 0: KV heads are walked in groups of 8 (one per XCD), see map_block
   float scale;
 };
 
@@ -45,6 +46,32 @@ __device__ __forceinline__ float max_across_halves(float v) {
 __device__ __forceinline__ float sum_across_halves(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// (blockIdx.x, blockIdx.y) -> (KV head, batch, row tile).  Workgroups are handed out x-fastest and round-robin over
+// the 8 XCDs, each with its own L2.  The batches (query heads x row blocks) that read one KV head's K/V stream
+// should run on one XCD and close in time, and an XCD should not hold more streams at once than its L2 can serve.
+// So KV heads are taken in groups of 8, one head per XCD: x = 8 * member + XCD slot runs over the batches of the
+// group's heads, y = group * tiles + tile, and a group's row tiles (longest first when causal) are all handed out
+// before the next group starts.  With 8 KV heads there is one group and this is "KV head = x % 8, all row tiles in
+// longest-first order"; with many KV heads (several layers stacked as heads) an XCD still streams one head at a
+// time instead of dozens.  kv_groups == 0 (head count not a multiple of 8): plain x = batch, y = tile.
+__device__ __forceinline__ void map_block(const AttnArgs& a, bool causal, int* kvh, int* batch, int* tile) {
+  const int x = blockIdx.x, y = blockIdx.y;
+  int ty;
+  if (a.kv_groups > 0) {
+    const int tiles = gridDim.y / a.kv_groups;
+    const int grp = y / tiles;
+    ty = y - grp * tiles;
+    *kvh = grp * 8 + (x & 7);
+    *batch = *kvh * a.batch_per_kv + (x >> 3);
+    *tile = causal ? tiles - 1 - ty : ty;
+  } else {
+    const int n_kv = a.n_batch / a.batch_per_kv;
+    *kvh = x % n_kv;
+    *batch = *kvh * a.batch_per_kv + x / n_kv;
+    *tile = causal ? (int)gridDim.y - 1 - y : y;
+  }
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -82,13 +109,11 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
   const int rw = lane & 31, h = lane >> 5;
   // grid = (batch, row tile, key chunk).  Workgroups are handed out x-fastest and round-robin over the 8
   // XCDs, so (1) every batch's longest causal row tiles start first and the short ones fill the tail,
-  // and (2) blockIdx.x % n_kv picks the KV head: the query heads that share a K/V stream run on the
-  // same XCD and find its tiles in that XCD's L2.
-  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  // and (2) map_batch puts the query heads that share a K/V stream on the same XCD, next to each other,
+  // where they find its tiles in that XCD's L2.
+  int kvh, batch, qt;
+  map_block(a, CAUSAL, &kvh, &batch, &qt);
   const int q0 = qt * C::BQ;
-  const int n_kv = a.n_batch / a.batch_per_kv;
-  const int kvh = blockIdx.x % n_kv;
-  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
   const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + C::BQ) : min(a.m, kv_begin + a.chunk);
@@ -351,11 +376,9 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int rw = lane & 31, h = lane >> 5;
-  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  int kvh, batch, qt;
+  map_block(a, CAUSAL, &kvh, &batch, &qt);
   const int q0 = qt * BQ;
-  const int n_kv = a.n_batch / a.batch_per_kv;
-  const int kvh = blockIdx.x % n_kv;
-  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
   const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + BQ) : min(a.m, kv_begin + a.chunk);
@@ -623,11 +646,9 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
   __shared__ float sP[RB * BK];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int kx = lane & 31, ch = lane >> 5;
-  const int qt = CAUSAL ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+  int kvh, batch, qt;
+  map_block(a, CAUSAL, &kvh, &batch, &qt);
   const int q0 = qt * RB;
-  const int n_kv = a.n_batch / a.batch_per_kv;
-  const int kvh = blockIdx.x % n_kv;
-  const int batch = kvh * a.batch_per_kv + blockIdx.x / n_kv;
   const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + RB) : min(a.m, kv_begin + a.chunk);
@@ -756,7 +777,19 @@ AttnArgs make_args(const AttnLaunch& l) {
   a.rows = l.rows; a.m = l.m; a.batch_per_kv = l.batch_per_kv; a.n_batch = l.n_batch;
   a.n_split = l.causal ? 1 : l.n_split;
   a.chunk = l.chunk; a.scale = l.scale;
+  a.kv_groups = 0;
   return a;
+}
+
+// Grid of an attention launch over `tiles` row tiles, and the matching kv_groups of the arguments.
+dim3 attn_grid(AttnArgs* a, int tiles) {
+  const int n_kv = a->n_batch / a->batch_per_kv;
+  if (n_kv % 8 == 0 && (long long)tiles * (n_kv / 8) <= 65535) {
+    a->kv_groups = n_kv / 8;
+    return dim3(8 * a->batch_per_kv, tiles * a->kv_groups, a->n_split);
+  }
+  a->kv_groups = 0;
+  return dim3(a->n_batch, tiles, a->n_split);
 }
 
 template <int D, bool CAUSAL, int NW, int KG = 1>
@@ -770,7 +803,7 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
     attr_set = true;
   }
   AttnArgs a = make_args(l);
-  dim3 grid(l.n_batch, (l.rows + C::BQ - 1) / C::BQ, a.n_split);
+  dim3 grid = attn_grid(&a, (l.rows + C::BQ - 1) / C::BQ);
   hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW, KG>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
@@ -786,7 +819,7 @@ hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
     attr_set = true;
   }
   AttnArgs a = make_args(l);
-  dim3 grid(l.n_batch, (l.rows + 255) / 256, a.n_split);
+  dim3 grid = attn_grid(&a, (l.rows + 255) / 256);
   hipLaunchKernelGGL((k_attn_bf16_dma<CAUSAL>), grid, dim3(512), LDS, s, a);
   return hipGetLastError();
 }
@@ -809,7 +842,7 @@ hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
 template <int D, bool CAUSAL>
 hipError_t run_f32(const AttnLaunch& l, hipStream_t s) {
   AttnArgs a = make_args(l);
-  dim3 grid(l.n_batch, (l.rows + 15) / 16, a.n_split);
+  dim3 grid = attn_grid(&a, (l.rows + 15) / 16);
   hipLaunchKernelGGL((k_attn_f32<D, CAUSAL>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }

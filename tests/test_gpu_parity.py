@@ -483,3 +483,41 @@ def test_fused_score_select_equals_the_two_calls(S, dtype, d, lens, ratio, n_sin
     else:
         with pytest.raises(S.SamKVError):
             S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, None, idx_b, None, ws)
+
+
+def test_layers_stacked_as_heads(S):
+    """Several layers in one call: every document's cache holds all layers as [(layer, KV head)][L][d] and the Q
+    tensors likewise.  The library sees 3 x Hkv KV heads; each layer's slice must agree with the oracle run on that
+    layer alone (query head h reads KV head h / G, which never leaves its layer)."""
+    import torch
+    lens, hq, hkv, d, ratio = [300, 77, 513], 4, 2, 128, 0.3
+    xs = [synth.make_small(90 + l, "bf16", lens, hq, hkv, d, 5, 7) for l in range(3)]
+    refs = [H.oracle_front(x, ratio) for x in xs]
+    m = int(refs[0].cu_k[-1])
+    cat = lambda arrs, axis=0: H.to_dev(np.concatenate(arrs, axis=axis), "bf16")
+    k = [cat([x.k[i] for x in xs]) for i in range(len(lens))]
+    v = [cat([x.v[i] for x in xs]) for i in range(len(lens))]
+    caches = S.Caches(k, v, 3 * hq)
+    q_tok = cat([x.q_tok for x in xs])
+    q_loc = cat([x.q_loc for x in xs], axis=1)
+    q_rec_np = [synth.make_q_rec(x.workload, l, m) for l, x in enumerate(xs)]
+    q_rec = cat(q_rec_np)
+    scale = 1.0 / math.sqrt(d)
+    buf = S.alloc_layer_buffers(caches, xs[0].workload.n_q_tok, ratio)
+    S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf)
+    torch.cuda.synchronize()
+    sg, idx = buf.scores.cpu().numpy().astype(np.float64), buf.idx.cpu().numpy()
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    G = hq // hkv
+    for l, (x, ref) in enumerate(zip(xs, refs)):
+        bound = H.score_error_bound(x, ref)
+        for i in range(len(lens)):
+            assert np.all(np.abs(sg[l * hkv:(l + 1) * hkv, cu[i]:cu[i + 1]] - ref.scores[i]) <= bound[i]), (l, i)
+        _, clean = H.compare_kept_sets(idx[l * hkv:(l + 1) * hkv], ref)
+        assert clean, f"layer {l}: no KV head reproduced the oracle's kept set"
+        heads = [h for h in range(hq) if h // G in clean]
+        o_ref, l_ref = O.attention(q_rec_np[l][heads], ref.k_c[clean], ref.v_c[clean], scale, True)
+        gh = [l * hq + h for h in heads]
+        H.check_attention(buf.rec_out[gh].cpu().numpy(), buf.rec_lse[gh].cpu().numpy(), o_ref, l_ref, "bf16", f"layer {l} recompute")
+        o_ref, l_ref = O.attention(x.q_tok[heads], ref.k_c[clean], ref.v_c[clean], scale, False)
+        H.check_attention(buf.q_out[gh].cpu().numpy(), buf.q_lse[gh].cpu().numpy(), o_ref, l_ref, "bf16", f"layer {l} query")
