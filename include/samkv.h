@@ -284,9 +284,11 @@ int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, 
  * launch (HIP events on `stream`).
  *   samkv_peak_mfma_bf16  n_blocks workgroups of 4 waves, each wave issues iters * 16 independent
  *                         v_mfma_f32_32x32x16_bf16: n_blocks * 4 * iters * 16 * 32768 flop.  sink: 4 bytes, untouched.
- *   samkv_peak_copy       dst[0..bytes) = src[0..bytes), 16-byte aligned, bytes a multiple of 16. */
+ *   samkv_peak_copy       dst[0..bytes) = src[0..bytes), 16-byte aligned, bytes a multiple of 16.
+ *   samkv_peak_read       reads src[0..bytes) once (16-byte aligned, a multiple of 16); sink: 4 bytes, untouched. */
 int samkv_peak_mfma_bf16(float* sink, int32_t n_blocks, int32_t iters, void* stream);
 int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream);
+int samkv_peak_read(const void* src, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

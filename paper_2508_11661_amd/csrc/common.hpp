@@ -78,6 +78,7 @@ hipError_t launch_filter_expand(const int32_t* sel, const int32_t* bidx, const I
 
 hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, hipStream_t s);
 hipError_t launch_peak_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+hipError_t launch_peak_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 
 struct GatherLaunch {
   int n_ctx, hkv, row_bytes, m_total, max_k;

@@ -596,6 +596,11 @@ int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream) {
   return dev(launch_peak_copy(src, dst, bytes, static_cast<hipStream_t>(stream)));
 }
 
+int samkv_peak_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (src == nullptr || sink == nullptr || bytes < 16 || bytes % 16 != 0 || ((uintptr_t)src % 16) != 0) return SAMKV_EINVAL;
+  return dev(launch_peak_read(src, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)));
+}
+
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
                          void* ws, size_t ws_bytes, void* stream) {

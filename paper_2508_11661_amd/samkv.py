@@ -22,7 +22,7 @@ EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
-           "samkv_kv_update", "samkv_peak_mfma_bf16", "samkv_peak_copy")
+           "samkv_kv_update", "samkv_peak_mfma_bf16", "samkv_peak_copy", "samkv_peak_read")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
 
@@ -93,6 +93,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_peak_mfma_bf16.argtypes = [vp, i32, i32, vp]
     lib.samkv_peak_copy.restype = ctypes.c_int
     lib.samkv_peak_copy.argtypes = [vp, vp, sz, vp]
+    lib.samkv_peak_read.restype = ctypes.c_int
+    lib.samkv_peak_read.argtypes = [vp, sz, vp, vp]
     lib.samkv_kv_update.restype = ctypes.c_int
     lib.samkv_kv_update.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     return lib
@@ -179,6 +181,13 @@ def samkv_peak_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
     assert dst.numel() * dst.element_size() == nbytes
     _check(_lib.samkv_peak_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "samkv_peak_copy")
     return 2 * nbytes
+
+
+def samkv_peak_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Launches the plain read micro-kernel; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(_lib.samkv_peak_read(_ptr(src), nbytes, _ptr(sink), _stream()), "samkv_peak_read")
+    return nbytes
 
 
 def samkv_kept_count(length: int, ratio: float) -> int:
