@@ -83,32 +83,46 @@ def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
     from paper_2508_11661_amd import synth
 
     w = layer.workload
-    t0, c0 = time.perf_counter(), time.process_time()
     n = len(layer.k)
-    q_hat = O.personalized_query(layer.q_tok, layer.q_loc, n)
-    scores = O.score(q_hat, layer.k)
-    idx, cu_k = O.select(scores, ratio)
-    k_c, v_c = O.gather(layer.k, layer.v, idx, cu_k)
-    t_front = time.perf_counter() - t0
-    m = int(cu_k[-1])
     scale = 1.0 / math.sqrt(w.head_dim)
-    q_rec = synth.make_q_rec(w, layer.layer, m)
     rng = np.random.default_rng(0)
-    if n_sample_rows >= m:
-        rows, frac = None, 1.0
-    else:
-        rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, size=n_sample_rows - 2)]))
-        frac = float((rows + 1).sum()) / (m * (m + 1) / 2)
-    t1 = time.perf_counter()
-    O.attention(q_rec, k_c, v_c, scale, True, rows=rows)
-    t_rec = (time.perf_counter() - t1) / frac
-    t2 = time.perf_counter()
-    O.attention(layer.q_tok, k_c, v_c, scale, False)
-    t_q = time.perf_counter() - t2
-    wall = time.perf_counter() - t0
+
+    def one_pass():
+        """One pass of the oracle over the layer; returns (extrapolated seconds, rows sampled or None, m, fraction)."""
+        t0 = time.perf_counter()
+        q_hat = O.personalized_query(layer.q_tok, layer.q_loc, n)
+        scores = O.score(q_hat, layer.k)
+        idx, cu_k = O.select(scores, ratio)
+        k_c, v_c = O.gather(layer.k, layer.v, idx, cu_k)
+        t_front = time.perf_counter() - t0
+        m = int(cu_k[-1])
+        q_rec = synth.make_q_rec(w, layer.layer, m)
+        if n_sample_rows >= m:
+            rows, frac = None, 1.0
+        else:
+            rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, size=n_sample_rows - 2)]))
+            frac = float((rows + 1).sum()) / (m * (m + 1) / 2)
+        t1 = time.perf_counter()
+        O.attention(q_rec, k_c, v_c, scale, True, rows=rows)
+        t_rec = (time.perf_counter() - t1) / frac
+        t2 = time.perf_counter()
+        O.attention(layer.q_tok, k_c, v_c, scale, False)
+        t_q = time.perf_counter() - t2
+        return t_front + t_rec + t_q, rows, m, frac
+
+    # a small layer is timed over as many whole passes as about ten seconds hold, a large one over one sampled pass
+    w0, c0 = time.perf_counter(), time.process_time()
+    totals = []
+    while True:
+        total, rows, m, frac = one_pass()
+        totals.append(total)
+        spent = time.perf_counter() - w0
+        if rows is not None or spent >= 10.0 or spent + spent / len(totals) > budget_s:
+            break
+    wall = time.perf_counter() - w0
     cores = max(1, round((time.process_time() - c0) / wall))
-    total = t_front + t_rec + t_q
-    sample = ("whole layer, every step of the path" if rows is None else
+    total = sum(totals) / len(totals)
+    sample = (f"whole layer, every step of the path, mean of {len(totals)} passes" if rows is None else
               f"score/select/gather/query attention in full; recompute attention on {len(rows)} of {m} rows per "
               f"head ({frac:.3%} of the causal pairs), time extrapolated by pair count")
     return {"value": sum(layer.lens) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
