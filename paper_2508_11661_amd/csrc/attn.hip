@@ -48,6 +48,36 @@ __device__ __forceinline__ float sum_across_halves(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Writes a wave's 32 x D block of normalised output rows.  In the accumulator layout a lane holds 4-float pieces of
+// ONE row (row = lane % 32), so a direct store instruction scatters 32-byte pieces over 32 rows; issuing the 4 D / 32
+// of them takes a few microseconds, which a short workgroup feels.  The block is therefore turned through LDS (the
+// wave's own `lds` area of 32 rows of D * 4 + 16 bytes; the pad keeps the 16 lanes of a write phase on distinct
+// banks) and leaves as whole rows, 1 KB per instruction.  Only this wave touches the area, and a wave's LDS
+// operations execute in order, so no barrier is needed.  dst points at the wave's first row; rows >= n_valid are
+// not written.
+template <int D>
+__device__ __forceinline__ void store_rows_via_lds(const f32x16 (&o)[D / 32], float inv, float* dst, int n_valid, char* lds,
+                                                   int lane) {
+  constexpr int RS = D * 4 + 16, LPR = D / 4, RPI = 64 / LPR;
+  const int rw = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int dvb = 0; dvb < D / 32; ++dvb)
+#pragma unroll
+    for (int j4 = 0; j4 < 4; ++j4) {
+      f32x4 x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
+      *reinterpret_cast<f32x4*>(lds + rw * RS + (dvb * 32 + 8 * j4 + 4 * h) * 4) = x;
+    }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int i = 0; i < 32 / RPI; ++i) {
+    const int row = i * RPI + lane / LPR;
+    const f32x4 x = *reinterpret_cast<const f32x4*>(lds + row * RS + (lane % LPR) * 16);
+    if (row < n_valid) *reinterpret_cast<f32x4*>(dst + (size_t)row * D + (lane % LPR) * 4) = x;
+  }
+}
+
 // (blockIdx.x, blockIdx.y) -> (KV head, batch, row tile).  Workgroups are handed out x-fastest and round-robin over
 // the 8 XCDs, each with its own L2.  The batches (query heads x row blocks) that read one KV head's K/V stream
 // should run on one XCD and close in time, and an XCD should not hold more streams at once than its L2 can serve.
@@ -315,29 +345,38 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
 
   const float l_tot = sum_across_halves(l_run);
   const float inv = 1.f / l_tot;
-  if (r < a.rows) {
-    const size_t row_id = (size_t)batch * a.rows + r;
-    float* op;
-    float* lp;
-    if (a.n_split > 1) {
-      const size_t prow = (size_t)split * a.n_batch * a.rows + row_id;
-      op = a.part_o + prow * D;
-      lp = a.part_lse + prow;
-    } else {
-      op = a.out + row_id * D;
-      lp = a.lse + row_id;
-    }
-#pragma unroll
-    for (int dvb = 0; dvb < NV; ++dvb)
-#pragma unroll
-      for (int j4 = 0; j4 < 4; ++j4) {
-        f32x4 x;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
-        *reinterpret_cast<f32x4*>(op + dvb * 32 + 8 * j4 + 4 * h) = x;
-      }
-    if (h == 0) *lp = (m_run + __log2f(l_tot)) * kLn2;
+  const size_t row0 = (size_t)batch * a.rows + wave_first;
+  float* op0;
+  float* lp0;
+  if (a.n_split > 1) {
+    const size_t prow = (size_t)split * a.n_batch * a.rows + row0;
+    op0 = a.part_o + prow * D;
+    lp0 = a.part_lse + prow;
+  } else {
+    op0 = a.out + row0 * D;
+    lp0 = a.lse + row0;
   }
+  // The wave's rows leave as whole rows through an LDS area of its own where the tile buffers have room for one per
+  // storing wave (every read of the tiles lies behind the loop's last barrier; with two key groups the area is the
+  // row group's merge area, which only this wave still touches); otherwise straight from the accumulator layout.
+  constexpr int TURN = 32 * (D * 4 + 16);
+  if constexpr (C::RG * TURN <= C::LDS_BYTES) {
+    store_rows_via_lds<D>(o, inv, op0, a.rows - wave_first, smem + rg * TURN, lane);
+  } else {
+    if (r < a.rows) {
+      float* op = op0 + (size_t)rw * D;
+#pragma unroll
+      for (int dvb = 0; dvb < NV; ++dvb)
+#pragma unroll
+        for (int j4 = 0; j4 < 4; ++j4) {
+          f32x4 x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
+          *reinterpret_cast<f32x4*>(op + dvb * 32 + 8 * j4 + 4 * h) = x;
+        }
+    }
+  }
+  if (r < a.rows && h == 0) lp0[rw] = (m_run + __log2f(l_tot)) * kLn2;
 }
 
 // ------------------------------------------------------ bf16, d = 128, asynchronous tile loads (LDS DMA)
