@@ -51,30 +51,36 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 // Writes a wave's 32 x D block of normalised output rows.  In the accumulator layout a lane holds 4-float pieces of
 // ONE row (row = lane % 32), so a direct store instruction scatters 32-byte pieces over 32 rows; issuing the 4 D / 32
 // of them takes a few microseconds, which a short workgroup feels.  The block is therefore turned through LDS (the
-// wave's own `lds` area of 32 rows of D * 4 + 16 bytes; the pad keeps the 16 lanes of a write phase on distinct
-// banks) and leaves as whole rows, 1 KB per instruction.  Only this wave touches the area, and a wave's LDS
-// operations execute in order, so no barrier is needed.  dst points at the wave's first row; rows >= n_valid are
-// not written.
-template <int D>
+// wave's own `lds` area; rows of D * 4 + 16 bytes, the pad keeps the 16 lanes of a write phase on distinct banks)
+// and leaves as whole rows, 1 KB per instruction.  PARTS = 1 turns the 32 rows at once (area of 32 rows), PARTS = 2
+// in two passes of 16 rows (area of 16 rows).  Only this wave touches the area, and a wave's LDS operations execute
+// in order, so no workgroup barrier is needed.  dst points at the wave's first row; rows >= n_valid are not written.
+template <int D, int PARTS = 1>
 __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&o)[D / 32], float inv, float* dst, int n_valid, char* lds,
                                                    int lane) {
-  constexpr int RS = D * 4 + 16, LPR = D / 4, RPI = 64 / LPR;
+  constexpr int RS = D * 4 + 16, LPR = D / 4, RPI = 64 / LPR, ROWS = 32 / PARTS;
   const int rw = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int dvb = 0; dvb < D / 32; ++dvb)
+  for (int part = 0; part < PARTS; ++part) {
+    if (PARTS == 1 || rw / ROWS == part) {
 #pragma unroll
-    for (int j4 = 0; j4 < 4; ++j4) {
-      f32x4 x;
+      for (int dvb = 0; dvb < D / 32; ++dvb)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
-      *reinterpret_cast<f32x4*>(lds + rw * RS + (dvb * 32 + 8 * j4 + 4 * h) * 4) = x;
+        for (int j4 = 0; j4 < 4; ++j4) {
+          f32x4 x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
+          *reinterpret_cast<f32x4*>(lds + (rw % ROWS) * RS + (dvb * 32 + 8 * j4 + 4 * h) * 4) = x;
+        }
     }
-  __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int i = 0; i < 32 / RPI; ++i) {
-    const int row = i * RPI + lane / LPR;
-    const f32x4 x = *reinterpret_cast<const f32x4*>(lds + row * RS + (lane % LPR) * 16);
-    if (row < n_valid) *reinterpret_cast<f32x4*>(dst + (size_t)row * D + (lane % LPR) * 4) = x;
+    for (int i = 0; i < ROWS / RPI; ++i) {
+      const int lrow = i * RPI + lane / LPR, row = part * ROWS + lrow;
+      const f32x4 x = *reinterpret_cast<const f32x4*>(lds + lrow * RS + (lane % LPR) * 16);
+      if (row < n_valid) *reinterpret_cast<f32x4*>(dst + (size_t)row * D + (lane % LPR) * 4) = x;
+    }
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -650,29 +656,21 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
 
   const float l_tot = sum_across_halves(l_run);
   const float inv = 1.f / l_tot;
-  if (r < a.rows) {
-    const size_t row_id = (size_t)batch * a.rows + r;
-    float* op;
-    float* lp;
-    if (a.n_split > 1) {
-      const size_t prow = (size_t)split * a.n_batch * a.rows + row_id;
-      op = a.part_o + prow * D;
-      lp = a.part_lse + prow;
-    } else {
-      op = a.out + row_id * D;
-      lp = a.lse + row_id;
-    }
-#pragma unroll
-    for (int dvb = 0; dvb < NV; ++dvb)
-#pragma unroll
-      for (int j4 = 0; j4 < 4; ++j4) {
-        f32x4 x;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = o[dvb][4 * j4 + e] * inv;
-        *reinterpret_cast<f32x4*>(op + dvb * 32 + 8 * j4 + 4 * h) = x;
-      }
-    if (h == 0) *lp = (m_ref + __log2f(l_tot)) * kLn2;
+  const size_t row0 = (size_t)batch * a.rows + wave_first;
+  float* op0;
+  float* lp0;
+  if (a.n_split > 1) {
+    const size_t prow = (size_t)split * a.n_batch * a.rows + row0;
+    op0 = a.part_o + prow * D;
+    lp0 = a.part_lse + prow;
+  } else {
+    op0 = a.out + row0 * D;
+    lp0 = a.lse + row0;
   }
+  // whole rows through the wave's 12 KB share of the tile slots (free: the last step ended with every request
+  // landed and a barrier), 16 rows at a time
+  store_rows_via_lds<D, 2>(o, inv, op0, a.rows - wave_first, smem + wave * (2 * NSLOT * TILE / NW), lane);
+  if (r < a.rows && h == 0) lp0[rw] = (m_ref + __log2f(l_tot)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------- f32
