@@ -125,9 +125,9 @@ __global__ void k_qtilde(const float* que, const float* bias, const float* loc, 
 // Q caches of all documents pass through that one workgroup, so this is for inputs of up to about a megabyte per
 // head, where launch latency and not bandwidth is what the three launches cost).  Writes Eq. 1 per QUERY head,
 // qhat[i][h][:]; k_score folds the heads of a KV group.
-//   1. Q_que[h]: the 16 waves split the user query's rows; partial sums meet in LDS.
-//   2. wave w takes documents w, w + 16, ...: mean of the document's local rows, |cos| with Q_que.
-//   3. bias = sum_j w_j Q_loc_j, then Q^_i = Q_que + (bias - w_i Q_loc_i) / (N - 1).
+//   1. wave w takes documents w, w + 16, ...: mean of the document's local rows, into LDS.
+//   2. Q_que[h]: the 16 waves split the user query's rows (requested ahead of step 1); partial sums meet in LDS.
+//   3. w_j = |cos(Q_que, Q_loc_j)|, bias = sum_j w_j Q_loc_j, then Q^_i = Q_que + (bias - w_i Q_loc_i) / (N - 1).
 template <bool BF16, int D>
 __global__ __launch_bounds__(1024) void k_prologue(const void* q_tok, int n_q_tok, const void* q_loc, int w_loc, int n_ctx,
                                                    int hq, int with_bias, float* qhat) {
@@ -144,24 +144,33 @@ __global__ __launch_bounds__(1024) void k_prologue(const void* q_tok, int n_q_to
   const int h = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int sub = lane % LPR, rgp = lane / LPR;
 
-  // acc += rows first, first + step, ... (< n_rows) of `src`, sixteen 16-byte loads in flight per lane
+  // acc += rows r0, r0 + step, ... (< n_rows) of `src`, U 16-byte loads in flight per lane; the loads of the first
+  // batch can be issued ahead (issue_rows) and consumed later (take_rows), with other loads in between
+  auto issue_rows = [&](const char* src, int r0, int step, int n_rows, auto& x) {
+    constexpr int U = sizeof(x) / sizeof(x[0]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = r0 + u * step;
+      x[u] = *reinterpret_cast<const u32x4*>(src + (size_t)(r < n_rows ? r : n_rows - 1) * ROW_BYTES);
+    }
+  };
+  auto take_rows = [&](int r0, int step, int n_rows, const auto& x, float* acc) {
+    constexpr int U = sizeof(x) / sizeof(x[0]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[EPL];
+      unpack16<BF16>(x[u], f);
+      const float keep = (r0 + u * step < n_rows) ? 1.f : 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = fmaf(f[e], keep, acc[e]);
+    }
+  };
   auto add_rows = [&](const char* src, int first, int step, int n_rows, float* acc) {
     constexpr int U = 16;
     for (int r0 = first; r0 < n_rows; r0 += U * step) {
       u32x4 x[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int r = r0 + u * step;
-        x[u] = *reinterpret_cast<const u32x4*>(src + (size_t)(r < n_rows ? r : n_rows - 1) * ROW_BYTES);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float f[EPL];
-        unpack16<BF16>(x[u], f);
-        const float keep = (r0 + u * step < n_rows) ? 1.f : 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(f[e], keep, acc[e]);
-      }
+      issue_rows(src, r0, step, n_rows, x);
+      take_rows(r0, step, n_rows, x, acc);
     }
   };
   // sum over the row groups of a wave: lanes that differ in the bits above log2(LPR)
@@ -171,12 +180,32 @@ __global__ __launch_bounds__(1024) void k_prologue(const void* q_tok, int n_q_to
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
   };
+  // The user query's rows and the documents' local rows are independent inputs: the first batch of the former is
+  // requested before the latter are pooled, so the two memory round trips overlap.
+  constexpr int UQ = 2;
+  const char* tok_src = static_cast<const char*>(q_tok) + (size_t)h * n_q_tok * ROW_BYTES + sub * 16;
+  const int tok_first = wave * RPW + rgp, tok_step = 16 * RPW;
+  u32x4 xq[UQ];
+  issue_rows(tok_src, tok_first, tok_step, n_q_tok, xq);
+  if (with_bias) {
+    for (int j = wave; j < n_ctx; j += 16) {
+      const char* src = static_cast<const char*>(q_loc) + ((size_t)j * hq + h) * w_loc * ROW_BYTES + sub * 16;
+      float acc[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+      add_rows(src, rgp, RPW, w_loc, acc);
+      fold_rows(acc);
+      if (rgp == 0)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_loc[j * D + sub * EPL + e] = acc[e] / (float)w_loc;
+    }
+  }
   {
-    const char* src = static_cast<const char*>(q_tok) + (size_t)h * n_q_tok * ROW_BYTES + sub * 16;
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    add_rows(src, wave * RPW + rgp, 16 * RPW, n_q_tok, acc);
+    take_rows(tok_first, tok_step, n_q_tok, xq, acc);
+    add_rows(tok_src, tok_first + UQ * tok_step, tok_step, n_q_tok, acc);
     fold_rows(acc);
     if (rgp == 0)
 #pragma unroll
@@ -198,24 +227,15 @@ __global__ __launch_bounds__(1024) void k_prologue(const void* q_tok, int n_q_to
     }
     na = group_sum<LPR>(na);
     for (int j = wave; j < n_ctx; j += 16) {
-      const char* src = static_cast<const char*>(q_loc) + ((size_t)j * hq + h) * w_loc * ROW_BYTES + sub * 16;
-      float acc[EPL];
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-      add_rows(src, rgp, RPW, w_loc, acc);
-      fold_rows(acc);
       float dot = 0.f, nb = 0.f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        acc[e] /= (float)w_loc;
-        dot = fmaf(qv[e], acc[e], dot);
-        nb = fmaf(acc[e], acc[e], nb);
+        const float lv = s_loc[j * D + sub * EPL + e];
+        dot = fmaf(qv[e], lv, dot);
+        nb = fmaf(lv, lv, nb);
       }
       dot = group_sum<LPR>(dot);
       nb = group_sum<LPR>(nb);
-      if (rgp == 0)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) s_loc[j * D + sub * EPL + e] = acc[e];
       if (lane == 0) {
         const float ra = sqrtf(na), rb = sqrtf(nb);
         s_w[j] = (ra < 1e-20f || rb < 1e-20f) ? 0.f : fabsf(dot / (ra * rb));
