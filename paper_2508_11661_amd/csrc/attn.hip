@@ -406,9 +406,12 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
 // A wave-wide DMA instruction fills 1 KB of LDS contiguously (lane i -> base + 16 i), i.e. four 256-byte
 // rows with no room for padding, so the tiles are stored unpadded and XOR-swizzled instead: the 16-byte
 // chunk c of row r sits at chunk position c ^ (r & 15) for K (16 consecutive rows of one fragment read
-// land in 16 different bank groups) and at c ^ 2 (r & 7) for V (the 4 rows x 32 B of a transposing read
-// land in disjoint bank ranges).  Which global chunk a lane fetches is free, so the swizzle costs nothing
-// on the load side; on the read side it is folded into per-lane address registers.
+// land in 16 different bank groups) and at c ^ 4 (r & 3) for V: a transposing read takes, from each of 8 rows,
+// the 64 bytes of one 4-chunk group, and LDS serves 32 lanes (4 of those rows) per cycle over its 64 banks, so the
+// 4 rows have to sit in the 4 different groups.  (c ^ 2 (r & 7) spreads 16 lanes' 32-byte pieces instead; the
+// counters showed every such read paying two extra cycles of bank conflicts.)  Which global chunk a lane fetches
+// is free, so the swizzle costs nothing on the load side; on the read side it is folded into per-lane address
+// registers.
 template <bool CAUSAL>
 __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   constexpr int D = 128, NW = 8, BQ = 32 * NW, BK = 64;
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
     const int row = 4 * (2 * wave + i) + (lane >> 4), pos = lane & 15;
     grow[i] = row;
     goff_k[i] = (uint32_t)(row * (D * 2) + ((pos ^ (row & 15)) * 16));
-    goff_v[i] = (uint32_t)(row * (D * 2) + ((pos ^ (2 * (row & 7))) * 16));
+    goff_v[i] = (uint32_t)(row * (D * 2) + ((pos ^ (4 * (row & 3))) * 16));
   }
   // The DMA is issued through inline assembly on purpose: the compiler then neither orders later LDS
   // reads behind it (it would drain every outstanding load before each fragment read) nor counts it in
@@ -481,7 +484,7 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int row = grow[i], pos = lane & 15;
-        const int src_chunk = is_v ? (pos ^ (2 * (row & 7))) : (pos ^ (row & 15));
+        const int src_chunk = is_v ? (pos ^ (4 * (row & 3))) : (pos ^ (row & 15));
         const uint32_t off = (uint32_t)(min(row, last) * (D * 2) + src_chunk * 16);
         dma16(tp, off, slot + (2 * wave + i) * 1024);
       }
@@ -497,8 +500,8 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
 #pragma unroll
     for (int dc = 0; dc < ND; ++dc) kaddr[dc] = (uint32_t)(rw * 256 + (((2 * dc + h) ^ x) * 16));
     const int i16 = lane & 15, q2 = (lane >> 4) & 1;
-    const int vrow = 4 * h + (i16 >> 2);       // + kb*32 + s2*16 (+8): multiples of 8, do not change row & 7
-    const int xv = 2 * (vrow & 7);
+    const int vrow = 4 * h + (i16 >> 2);       // + kb*32 + s2*16 (+8): multiples of 8, do not change row & 3
+    const int xv = 4 * (vrow & 3);
 #pragma unroll
     for (int dvb = 0; dvb < NV; ++dvb) {
       const int c = 4 * dvb + 2 * q2 + ((i16 & 3) >> 1);
