@@ -31,7 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 FP32_VALU_PEAK_TFLOPS = 157.3
 KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")          # the five entry points of the path
-STEP = ("score_select", "gather", "recompute_attn", "query_attn")                # what a step launches: the first two fused
+STEP = ("score_select_gather", "recompute_attn", "query_attn")                   # what a step launches: the first three fused
+EXTRA = ("score_select",)                                                        # also timed per call, outside the step
 
 
 def algorithmic_work(w, lens, m, n_q_tok):
@@ -47,6 +48,9 @@ def algorithmic_work(w, lens, m, n_q_tok):
         # fused: K and the Q rows read once, only the kept positions written (the scores stay on chip)
         "score_select": {"bytes": tot * hkv * d * e + q_rows * d * e + m * hkv * 4, "flops": 2 * d * tot * hkv},
         "gather": {"bytes": m * hkv * (4 * d * e + 4), "flops": 0},
+        # score, selection and compaction in one call: the two above, the positions written once and read back on chip
+        "score_select_gather": {"bytes": tot * hkv * d * e + q_rows * d * e + m * hkv * (4 * d * e + 4),
+                                "flops": 2 * d * tot * hkv},
         "recompute_attn": {"bytes": (2 * hq + 2 * hkv) * m * d * e + hq * m * (d + 1) * 4,
                            "flops": 4 * hq * d * m * (m + 1) // 2},
         "query_attn": {"bytes": 2 * m * hkv * d * e + hq * n_q_tok * (d * e + (d + 1) * 4),
@@ -58,6 +62,7 @@ def read_traffic(workload, kernel: str):
     """HBM bytes per launch (read + write) of a kernel, from the committed rocprofv3 --pmc summary of this
     workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
     prefixes = {"score": ["k_score<"], "select": ["k_select"], "gather": ["k_gather<"], "score_select": ["k_score_select"],
+                "score_select_gather": ["k_score_select"],
                 "recompute_attn": ["k_attn_%s<%d, true" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<true" % workload.dtype],
                 "query_attn": ["k_attn_%s<%d, false" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<false" % workload.dtype],
                 }[kernel]
@@ -356,6 +361,8 @@ def main() -> int:
         "query_attn": lambda s, b: samkv.samkv_query_attn(s["q_tok"], b.k_c, b.v_c, scale, b.q_out, b.q_lse, b.ws),
         "score_select": lambda s, b: samkv.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, b.idx,
                                                               b.cu_k_dev, b.ws),
+        "score_select_gather": lambda s, b: samkv.samkv_score_select_gather(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0,
+                                                                            None, b.idx, b.cu_k_dev, b.k_c, b.v_c, b.ws),
     }
 
     def step(i, events=None, only=None, names=STEP):
@@ -399,10 +406,11 @@ def main() -> int:
     ms_per_step = elapsed / args.steps * 1e3
 
     # untimed again: every call bracketed, for the per-call table (the step's fused call, then the five entry points)
-    events = {name: [] for name in STEP + KERNELS}
+    events = {name: [] for name in STEP + KERNELS + EXTRA}
     for i in range(min(args.steps, 50)):
         step(args.warmup + args.steps + i, events)
         step(args.warmup + args.steps + i, events, names=KERNELS)
+        step(args.warmup + args.steps + i, events, names=EXTRA)
     torch.cuda.synchronize()
     events[dom] = dom_events[dom]          # the dominant call's figure is the one from the timed region
 
@@ -457,7 +465,7 @@ def main() -> int:
 
     work = algorithmic_work(w, w.lens, m, w.n_q_tok)
     per_kernel = {}
-    for name in STEP + tuple(n for n in KERNELS if n not in STEP):
+    for name in STEP + tuple(n for n in KERNELS + EXTRA if n not in STEP):
         ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
         gbs = work[name]["bytes"] * layers_per_call / (ms * 1e-3) / 1e9
         tfl = work[name]["flops"] * layers_per_call / (ms * 1e-3) / 1e12
@@ -471,7 +479,7 @@ def main() -> int:
     ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) * layers_per_call / (ss_ms * 1e-3) / 1e9
     per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
                                   "note": "the two separate calls as one K-streaming stage, for comparison with the "
-                                          "fused score_select call that the timed step launches"}
+                                          "fused calls (score_select, and score_select_gather that the timed step launches)"}
     if dom.endswith("attn") and w.dtype == "bf16":
         roof = {"kernel": dom, "bound": "mfma", "achieved": per_kernel[dom]["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS, 4)}

@@ -123,6 +123,16 @@ int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_
                        int32_t w_loc, float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx,
                        int32_t* cu_k_dev, int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream);
 
+/* samkv_score_select and samkv_gather (Sec. 3.2: score, select, concatenate the kept rows) as one call: the workgroup
+ * that has selected a (document, KV head) row also copies its kept K and V rows into the compacted cache, so short
+ * inputs pay one launch instead of two.  Arguments and results as in the two calls (idx is written as well; k_c and
+ * v_c [Hkv][M][d], dtype of caches, must not be NULL; caches->v is read).  Documents longer than 8192 tokens fall back
+ * to the separate kernels and need `scores` as their buffer. */
+int samkv_score_select_gather(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                              int32_t w_loc, float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx,
+                              int32_t* cu_k_dev, int32_t* cu_k_host, void* k_c, void* v_c, void* ws, size_t ws_bytes,
+                              void* stream);
+
 /* Sec. 3.2, dynamic Top-P (Eq. 2 and Eq. 3).  HOST arithmetic on a handful of scalars, no device work:
  *   P^(n)_i = (s_max - s_anc) / (s_max - s_min)  if s_min < s_anc <= s_max, else 0                  (Eq. 2)
  *   P_i     = mean over the n_layers stable layers of P^(n)_i                                        (Eq. 3)

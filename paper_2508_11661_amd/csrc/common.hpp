@@ -58,10 +58,8 @@ struct SelectLaunch {
 };
 hipError_t launch_select(const SelectLaunch& a, const IntTable& cu_len, const IntTable& cu_k, hipStream_t s);
 
-// Score and selection in one pass over K (rows of at most kFusedMaxLen tokens): a.scores may be null.
 constexpr int kFusedMaxLen = 8192;
-hipError_t launch_score_select(const ScoreLaunch& a, const SelectLaunch& sl, const PtrTable& k, const IntTable& cu_len,
-                               const IntTable& cu_k, hipStream_t s);
+constexpr int kFusedGatherMaxRows = 2048;  // (document, KV head) rows up to which the fused call also compacts in-kernel
 
 hipError_t launch_block_scores(const float* scores, const IntTable& cu_len, const IntTable& cu_blk, int n_ctx, int hkv,
                                int total_len, int block, float* bscores, hipStream_t s);
@@ -88,6 +86,11 @@ struct GatherLaunch {
 };
 hipError_t launch_gather(const GatherLaunch& a, const PtrTable& k, const PtrTable& v, const IntTable& cu_len,
                          const IntTable& cu_k, hipStream_t s);
+// Score and selection in one pass over K (rows of at most kFusedMaxLen tokens): a.scores may be null.  With `ga`
+// and `v` the same workgroups also compact the kept K and V rows (what launch_gather does).
+hipError_t launch_score_select(const ScoreLaunch& a, const SelectLaunch& sl, const PtrTable& k, const IntTable& cu_len,
+                               const IntTable& cu_k, hipStream_t s, const GatherLaunch* ga = nullptr,
+                               const PtrTable* v = nullptr);
 // Q-cache variant: a.k_c receives [Hq][M][d]; q holds per-document [Hq][L_i][d]
 hipError_t launch_gather_q(const GatherLaunch& a, const PtrTable& q, const IntTable& cu_len, const IntTable& cu_k,
                            int hq, hipStream_t s);

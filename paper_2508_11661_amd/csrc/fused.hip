@@ -10,10 +10,13 @@
 namespace samkv {
 namespace {
 
-template <bool BF16, int D, int E, int NT>
-__global__ __launch_bounds__(NT) void k_score_select(PtrTable kt, IntTable cu_len, IntTable cu_k, const float* qsrc, int heads,
-                                                     int group, int total_len, int m_total, int n_ctx, int n_sink,
-                                                     int n_local, float* scores, int32_t* idx, int32_t* cu_k_dev) {
+// GATHER: the workgroup also copies the row's kept K and V rows into the compacted cache (samkv_gather's job for
+// this document and KV head): the positions it has just written are read back after a workgroup-scope fence.
+template <bool BF16, int D, int E, int NT, bool GATHER>
+__global__ __launch_bounds__(NT) void k_score_select(PtrTable kt, PtrTable vt, IntTable cu_len, IntTable cu_k, const float* qsrc,
+                                                     int heads, int group, int total_len, int m_total, int n_ctx, int n_sink,
+                                                     int n_local, float* scores, int32_t* idx, int32_t* cu_k_dev, char* k_c,
+                                                     char* v_c) {
   constexpr int EPL = BF16 ? 8 : 4;
   constexpr int LPR = D / EPL;
   constexpr int ROWS_PER_WAVE = (64 / LPR) * 8 * 2;
@@ -45,44 +48,90 @@ __global__ __launch_bounds__(NT) void k_score_select(PtrTable kt, IntTable cu_le
 #pragma unroll
   for (int e = 0; e < E; ++e) key[e] = (p0 + e < L) ? order_key(s_sc[p0 + e]) : 0u;
   force_keys<E>(key, p0, L, n_sink, n_local);
-  select_from_keys<E, NT>(key, p0, L, k, idx + (size_t)g * m_total + cu_k.v[i], cnt, wsum);
+  int32_t* ip = idx + (size_t)g * m_total + cu_k.v[i];
+  select_from_keys<E, NT>(key, p0, L, k, ip, cnt, wsum);
+
+  if (GATHER) {
+    __threadfence_block();
+    __syncthreads();
+    // LPR lanes copy one K row and one V row; U rows per thread in flight
+    constexpr int RPP = NT / LPR, U = 4;
+    const int rg = t / LPR;
+    const char* vsrc = static_cast<const char*>(vt.p[i]) + (size_t)g * L * ROW_BYTES + sub * 16;
+    const size_t out0 = ((size_t)g * m_total + cu_k.v[i]) * ROW_BYTES + sub * 16;
+    for (int r0 = rg; r0 < k; r0 += RPP * U) {
+      u32x4 xk[U], xv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = r0 + u * RPP;
+        int pos = ip[r < k ? r : k - 1];
+        pos = pos < 0 ? 0 : (pos >= L ? L - 1 : pos);
+        xk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (size_t)pos * ROW_BYTES));
+        xv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vsrc + (size_t)pos * ROW_BYTES));
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = r0 + u * RPP;
+        if (r < k) {
+          __builtin_nontemporal_store(xk[u], reinterpret_cast<u32x4*>(k_c + out0 + (size_t)r * ROW_BYTES));
+          __builtin_nontemporal_store(xv[u], reinterpret_cast<u32x4*>(v_c + out0 + (size_t)r * ROW_BYTES));
+        }
+      }
+    }
+  }
 }
 
 template <bool BF16, int D, int E, int NT>
 hipError_t run(const ScoreLaunch& a, const SelectLaunch& sl, const QuerySrc& q, const PtrTable& k, const IntTable& cu_len,
-               const IntTable& cu_k, hipStream_t s) {
+               const IntTable& cu_k, const GatherLaunch* ga, const PtrTable* v, hipStream_t s) {
   const size_t lds = (size_t)E * NT * sizeof(float);
-  hipLaunchKernelGGL((k_score_select<BF16, D, E, NT>), dim3(a.n_ctx, a.hkv), dim3(NT), lds, s, k, cu_len, cu_k, q.q, q.heads,
-                     q.group, a.total_len, sl.m_total, a.n_ctx, sl.n_sink, sl.n_local, a.scores, sl.idx, sl.cu_k_dev);
+  if (ga != nullptr)
+    hipLaunchKernelGGL((k_score_select<BF16, D, E, NT, true>), dim3(a.n_ctx, a.hkv), dim3(NT), lds, s, k, *v, cu_len, cu_k, q.q,
+                       q.heads, q.group, a.total_len, sl.m_total, a.n_ctx, sl.n_sink, sl.n_local, a.scores, sl.idx,
+                       sl.cu_k_dev, static_cast<char*>(ga->k_c), static_cast<char*>(ga->v_c));
+  else
+    hipLaunchKernelGGL((k_score_select<BF16, D, E, NT, false>), dim3(a.n_ctx, a.hkv), dim3(NT), lds, s, k, k, cu_len, cu_k, q.q,
+                       q.heads, q.group, a.total_len, sl.m_total, a.n_ctx, sl.n_sink, sl.n_local, a.scores, sl.idx,
+                       sl.cu_k_dev, nullptr, nullptr);
   return hipGetLastError();
 }
 
 template <bool BF16, int D>
 hipError_t run_len(const ScoreLaunch& a, const SelectLaunch& sl, const QuerySrc& q, const PtrTable& k,
-                   const IntTable& cu_len, const IntTable& cu_k, hipStream_t s) {
+                   const IntTable& cu_len, const IntTable& cu_k, const GatherLaunch* ga, const PtrTable* v, hipStream_t s) {
   // up to 4096 keys a row: 512 threads.  They halve the passes a wave makes over its share of the row's keys
   // (2.3 us less per call at 1024 keys, 4 % at 4096 keys than 256 threads); 1024 threads lose it again in the
   // selection's barriers.
-  if (a.max_len <= 1024) return run<BF16, D, 2, 512>(a, sl, q, k, cu_len, cu_k, s);
-  if (a.max_len <= 4096) return run<BF16, D, 8, 512>(a, sl, q, k, cu_len, cu_k, s);
-  return run<BF16, D, 32, 256>(a, sl, q, k, cu_len, cu_k, s);
+  if (a.max_len <= 1024) return run<BF16, D, 2, 512>(a, sl, q, k, cu_len, cu_k, ga, v, s);
+  if (a.max_len <= 4096) return run<BF16, D, 8, 512>(a, sl, q, k, cu_len, cu_k, ga, v, s);
+  return run<BF16, D, 32, 256>(a, sl, q, k, cu_len, cu_k, ga, v, s);
 }
 
 }  // namespace
 
 hipError_t launch_score_select(const ScoreLaunch& a, const SelectLaunch& sl, const PtrTable& k, const IntTable& cu_len,
-                               const IntTable& cu_k, hipStream_t s) {
-  if (a.max_len > kFusedMaxLen) {  // rows too long for LDS: the two kernels, through the caller's score buffer
+                               const IntTable& cu_k, hipStream_t s, const GatherLaunch* ga, const PtrTable* v) {
+  if (a.max_len > kFusedMaxLen) {  // rows too long for LDS: the separate kernels, through the caller's score buffer
     if (a.scores == nullptr) return hipErrorInvalidValue;
     hipError_t e = launch_score(a, k, cu_len, s);
-    return e != hipSuccess ? e : launch_select(sl, cu_len, cu_k, s);
+    if (e == hipSuccess) e = launch_select(sl, cu_len, cu_k, s);
+    if (e == hipSuccess && ga != nullptr) e = launch_gather(*ga, k, *v, cu_len, cu_k, s);
+    return e;
   }
   QuerySrc q;
   hipError_t e = launch_score_prologue(a, s, &q);
   if (e != hipSuccess) return e;
+  // With thousands of rows (many layers stacked as heads) the compaction is faster as its own streaming kernel
+  // (0.84 against 0.91 ms at 5120 rows); below that the row's workgroup does it and a launch is saved.
+  const GatherLaunch* in_kernel = (long long)a.n_ctx * a.hkv <= kFusedGatherMaxRows ? ga : nullptr;
   if (a.dtype == SAMKV_BF16)
-    return a.d == 128 ? run_len<true, 128>(a, sl, q, k, cu_len, cu_k, s) : run_len<true, 64>(a, sl, q, k, cu_len, cu_k, s);
-  return a.d == 128 ? run_len<false, 128>(a, sl, q, k, cu_len, cu_k, s) : run_len<false, 64>(a, sl, q, k, cu_len, cu_k, s);
+    e = a.d == 128 ? run_len<true, 128>(a, sl, q, k, cu_len, cu_k, in_kernel, v, s)
+                   : run_len<true, 64>(a, sl, q, k, cu_len, cu_k, in_kernel, v, s);
+  else
+    e = a.d == 128 ? run_len<false, 128>(a, sl, q, k, cu_len, cu_k, in_kernel, v, s)
+                   : run_len<false, 64>(a, sl, q, k, cu_len, cu_k, in_kernel, v, s);
+  if (e == hipSuccess && ga != nullptr && in_kernel == nullptr) e = launch_gather(*ga, k, *v, cu_len, cu_k, s);
+  return e;
 }
 
 }  // namespace samkv

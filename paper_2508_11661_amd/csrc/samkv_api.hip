@@ -217,9 +217,11 @@ int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, 
   return dev(launch_score(a, kt, s.cu_len, static_cast<hipStream_t>(stream)));
 }
 
-int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
-                       float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx, int32_t* cu_k_dev,
-                       int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
+// samkv_score_select, and with k_c/v_c the compaction as well
+static int score_select_common(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                               int32_t w_loc, float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx,
+                               int32_t* cu_k_dev, int32_t* cu_k_host, bool gather, void* k_c, void* v_c, void* ws,
+                               size_t ws_bytes, void* stream) {
   Shape s;
   ScoreLaunch a;
   PtrTable kt;
@@ -230,12 +232,42 @@ int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_
   IntTable cu_k;
   rc = kept_table(caches, ratio, n_sink, n_local, &cu_k);
   if (rc != SAMKV_OK) return rc;
+  PtrTable vt;
+  GatherLaunch ga;
+  if (gather) {
+    Shape s2;
+    rc = check_caches(caches, true, true, &s2);  // V is read as well
+    if (rc != SAMKV_OK) return rc;
+    if (k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
+    memset(&vt, 0, sizeof(vt));
+    for (int i = 0; i < s.n_ctx; ++i) vt.p[i] = caches->v[i];
+    ga.n_ctx = s.n_ctx; ga.hkv = s.hkv; ga.row_bytes = s.d * (s.dtype == SAMKV_BF16 ? 2 : 4);
+    ga.m_total = cu_k.v[s.n_ctx]; ga.idx = idx; ga.k_c = k_c; ga.v_c = v_c;
+    ga.max_k = 0;
+    for (int i = 0; i < s.n_ctx; ++i) ga.max_k = cu_k.v[i + 1] - cu_k.v[i] > ga.max_k ? cu_k.v[i + 1] - cu_k.v[i] : ga.max_k;
+  }
   if (cu_k_host != nullptr) memcpy(cu_k_host, cu_k.v, sizeof(int32_t) * (s.n_ctx + 1));
   SelectLaunch sl;
   sl.n_ctx = s.n_ctx; sl.hkv = s.hkv; sl.max_len = s.max_len; sl.total_len = s.total_len;
   sl.m_total = cu_k.v[s.n_ctx]; sl.n_sink = n_sink; sl.n_local = n_local;
   sl.scores = scores; sl.idx = idx; sl.cu_k_dev = cu_k_dev;
-  return dev(launch_score_select(a, sl, kt, s.cu_len, cu_k, static_cast<hipStream_t>(stream)));
+  return dev(launch_score_select(a, sl, kt, s.cu_len, cu_k, static_cast<hipStream_t>(stream), gather ? &ga : nullptr,
+                                 gather ? &vt : nullptr));
+}
+
+int samkv_score_select(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
+                       float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx, int32_t* cu_k_dev,
+                       int32_t* cu_k_host, void* ws, size_t ws_bytes, void* stream) {
+  return score_select_common(caches, q_tok, n_q_tok, q_loc, w_loc, ratio, n_sink, n_local, scores, idx, cu_k_dev, cu_k_host,
+                             false, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int samkv_score_select_gather(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                              int32_t w_loc, float ratio, int32_t n_sink, int32_t n_local, float* scores, int32_t* idx,
+                              int32_t* cu_k_dev, int32_t* cu_k_host, void* k_c, void* v_c, void* ws, size_t ws_bytes,
+                              void* stream) {
+  return score_select_common(caches, q_tok, n_q_tok, q_loc, w_loc, ratio, n_sink, n_local, scores, idx, cu_k_dev, cu_k_host,
+                             true, k_c, v_c, ws, ws_bytes, stream);
 }
 
 static int select_common(const float* scores, const samkv_caches* caches, const Shape& s, const IntTable& cu_k,

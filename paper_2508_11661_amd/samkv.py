@@ -18,7 +18,7 @@ SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
-           "samkv_score", "samkv_score_select", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
+           "samkv_score", "samkv_score_select", "samkv_score_select_gather", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
@@ -51,6 +51,9 @@ def _load() -> ctypes.CDLL:
     lib.samkv_score.argtypes = [cp, vp, i32, vp, i32, vp, vp, sz, vp]
     lib.samkv_score_select.restype = ctypes.c_int
     lib.samkv_score_select.argtypes = [cp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    lib.samkv_score_select_gather.restype = ctypes.c_int
+    lib.samkv_score_select_gather.argtypes = [cp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, ctypes.POINTER(i32), vp, vp,
+                                              vp, sz, vp]
     lib.samkv_topk_select.restype = ctypes.c_int
     lib.samkv_topk_select.argtypes = [vp, cp, f32, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_gather.restype = ctypes.c_int
@@ -222,6 +225,26 @@ def samkv_score_select(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torc
     _check(_lib.samkv_score_select(ctypes.byref(caches.c), _ptr(q_tok), n_q_tok, _ptr(q_loc), w_loc, ratio, n_sink,
                                    n_local, _ptr(scores), _ptr(idx), _ptr(cu_k_dev), cu_k_host, _ptr(ws),
                                    ws.numel() * ws.element_size(), _stream()), "samkv_score_select")
+    return list(cu_k_host)
+
+
+def samkv_score_select_gather(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor], ratio: float,
+                              n_sink: int, n_local: int, scores: Optional[torch.Tensor], idx: torch.Tensor,
+                              cu_k_dev: Optional[torch.Tensor], k_c: torch.Tensor, v_c: torch.Tensor,
+                              ws: torch.Tensor) -> List[int]:
+    """samkv_score_select and samkv_gather in one call; returns the host prefix sums cu_k."""
+    n_q_tok = int(q_tok.shape[1])
+    w_loc = int(q_loc.shape[2]) if q_loc is not None else 0
+    m = sum(samkv_kept_count(n, ratio) for n in caches.lens)
+    assert scores is None or (scores.dtype == torch.float32 and tuple(scores.shape) == (caches.n_kv_heads, caches.total_len))
+    assert idx.dtype == torch.int32 and tuple(idx.shape) == (caches.n_kv_heads, m)
+    for x in (k_c, v_c):
+        assert x.is_contiguous() and tuple(x.shape) == (caches.n_kv_heads, m, caches.head_dim) and x.dtype == q_tok.dtype
+    cu_k_host = (ctypes.c_int32 * (caches.n_ctx + 1))()
+    _check(_lib.samkv_score_select_gather(ctypes.byref(caches.c), _ptr(q_tok), n_q_tok, _ptr(q_loc), w_loc, ratio, n_sink,
+                                          n_local, _ptr(scores), _ptr(idx), _ptr(cu_k_dev), cu_k_host, _ptr(k_c),
+                                          _ptr(v_c), _ptr(ws), ws.numel() * ws.element_size(), _stream()),
+           "samkv_score_select_gather")
     return list(cu_k_host)
 
 
@@ -450,12 +473,13 @@ def hot_path(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor],
              ratio: float, scale: float, buf: LayerBuffers, n_sink: int = 0, n_local: int = 0,
              fused: bool = True) -> None:
     """One pass of the whole hot path of a layer: score, select, gather, recompute, query attention.  `fused`
-    scores and selects in one pass over K (same kept positions); otherwise the two separate calls."""
+    scores, selects and compacts in one call (same kept positions, same bytes); otherwise the three separate calls."""
     if fused:
-        samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, buf.scores, buf.idx, buf.cu_k_dev, buf.ws)
+        samkv_score_select_gather(caches, q_tok, q_loc, ratio, n_sink, n_local, buf.scores, buf.idx, buf.cu_k_dev,
+                                  buf.k_c, buf.v_c, buf.ws)
     else:
         samkv_score(caches, q_tok, q_loc, buf.scores, buf.ws)
         samkv_topk_select(buf.scores, caches, ratio, n_sink, n_local, buf.idx, buf.cu_k_dev, buf.ws)
-    samkv_gather(caches, buf.idx, ratio, buf.k_c, buf.v_c)
+        samkv_gather(caches, buf.idx, ratio, buf.k_c, buf.v_c)
     samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws)
     samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws)

@@ -115,6 +115,17 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_score_select(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu, None, 0, None) == -3
     assert L.samkv_score_select(ctypes.byref(_caches(S, lens=(8, 9000))), fake, 4, None, 0, 0.5, 0, 0, None, fake, None, cu,
                                 fake, 1 << 20, None) == -1   # rows beyond the fused kernel need the score buffer
+    # samkv_score_select_gather
+    assert L.samkv_score_select_gather(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu, None, fake, fake,
+                                       1 << 20, None) == -1      # no k_c
+    assert L.samkv_score_select_gather(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu, fake, None, fake,
+                                       1 << 20, None) == -1      # no v_c
+    assert L.samkv_score_select_gather(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, None, None, cu, fake, fake, fake,
+                                       1 << 20, None) == -1      # no idx
+    assert L.samkv_score_select_gather(ctypes.byref(_caches(S, v=False)), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu,
+                                       fake, fake, fake, 1 << 20, None) == -1   # V is read
+    assert L.samkv_score_select_gather(ctypes.byref(ok), fake, 4, None, 0, 0.5, 0, 0, fake, fake, None, cu, fake, fake, None,
+                                       0, None) == -3
     # samkv_topk_select
     assert L.samkv_topk_select(None, ctypes.byref(ok), 0.5, 0, 0, fake, None, cu, None, 0, None) == -1
     assert L.samkv_topk_select(fake, ctypes.byref(ok), 0.0, 0, 0, fake, None, cu, None, 0, None) == -1

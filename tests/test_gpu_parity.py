@@ -485,6 +485,50 @@ def test_fused_score_select_equals_the_two_calls(S, dtype, d, lens, ratio, n_sin
             S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, None, idx_b, None, ws)
 
 
+@pytest.mark.parametrize("dtype,d,lens,ratio,n_sink,n_local,hq,hkv", [
+    ("bf16", 128, [300, 77, 1025, 513], 0.3, 4, 8, 8, 2), ("bf16", 64, [1000, 1024, 5], 0.15, 0, 0, 8, 2),
+    ("f32", 128, [4096, 4097, 130], 0.1, 2, 2, 8, 2), ("f32", 64, [8192, 63, 2500], 0.2, 0, 8, 8, 2),
+    ("bf16", 128, [9000, 700], 0.05, 1, 1, 8, 2),  # longer than the fused kernel's rows: falls back to three launches
+    ("bf16", 64, [37 + (i % 5) for i in range(40)], 0.25, 1, 2, 64, 64),  # 2560 rows: compaction as its own kernel
+])
+def test_fused_score_select_gather_equals_the_separate_calls(S, dtype, d, lens, ratio, n_sink, n_local, hq, hkv):
+    """score + select + gather in one call: positions and compacted rows bit-identical to the separate calls, and the
+    compacted rows are exactly the source rows at the positions the call itself reports (checked on the host)."""
+    import torch
+    x = synth.make_small(83, dtype, lens, hq, hkv, d, 6, 9)
+    ref = H.oracle_front(x, ratio, n_sink, n_local)
+    caches = H.upload_caches(x)
+    q_tok, q_loc = H.to_dev(x.q_tok, dtype), H.to_dev(x.q_loc, dtype)
+    m = int(ref.cu_k[-1])
+    ws = _ws(S, x, x.workload.n_q_tok, m)
+    td = H.torch_dtype(dtype)
+    sc_a = torch.full((hkv, caches.total_len), float("nan"), device="cuda")
+    idx_a = torch.full((hkv, m), -1, dtype=torch.int32, device="cuda")
+    k_a, v_a = torch.zeros((hkv, m, d), dtype=td, device="cuda"), torch.zeros((hkv, m, d), dtype=td, device="cuda")
+    S.samkv_score_select(caches, q_tok, q_loc, ratio, n_sink, n_local, sc_a, idx_a, None, ws)
+    S.samkv_gather_v(caches, idx_a, ref.cu_k.tolist(), k_a, v_a)
+    sc_b = torch.full((hkv, caches.total_len), float("nan"), device="cuda")
+    idx_b = torch.full((hkv, m), -1, dtype=torch.int32, device="cuda")
+    k_b, v_b = torch.ones((hkv, m, d), dtype=td, device="cuda"), torch.ones((hkv, m, d), dtype=td, device="cuda")
+    cu_b = S.samkv_score_select_gather(caches, q_tok, q_loc, ratio, n_sink, n_local, sc_b, idx_b, None, k_b, v_b, ws)
+    assert cu_b == ref.cu_k.tolist()
+    assert torch.equal(sc_a, sc_b) and torch.equal(idx_a, idx_b)
+    assert torch.equal(k_a, k_b) and torch.equal(v_a, v_b)
+    H.compare_kept_sets(idx_b.cpu().numpy(), ref, n_sink, n_local)
+    idx_h = idx_b.cpu().numpy()
+    kc, vc = k_b.float().cpu().numpy(), v_b.float().cpu().numpy()
+    for i in range(len(lens)):
+        for g in range(hkv):
+            pos = idx_h[g, ref.cu_k[i]:ref.cu_k[i + 1]]
+            assert np.array_equal(kc[g, ref.cu_k[i]:ref.cu_k[i + 1]], x.k[i][g][pos])
+            assert np.array_equal(vc[g, ref.cu_k[i]:ref.cu_k[i + 1]], x.v[i][g][pos])
+    if max(lens) <= 8192:                           # without a score buffer
+        k_c, v_c = torch.zeros_like(k_b), torch.zeros_like(v_b)
+        idx_c = torch.full((hkv, m), -1, dtype=torch.int32, device="cuda")
+        S.samkv_score_select_gather(caches, q_tok, q_loc, ratio, n_sink, n_local, None, idx_c, None, k_c, v_c, ws)
+        assert torch.equal(idx_a, idx_c) and torch.equal(k_a, k_c) and torch.equal(v_a, v_c)
+
+
 def test_layers_stacked_as_heads(S):
     """Several layers in one call: every document's cache holds all layers as [(layer, KV head)][L][d] and the Q
     tensors likewise.  The library sees 3 x Hkv KV heads; each layer's slice must agree with the oracle run on that
