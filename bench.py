@@ -389,10 +389,11 @@ def main() -> int:
     # untimed: which call dominates (events around every call cost a few microseconds each, so the timed region
     # below carries them only around that one call)
     probe = {name: [] for name in STEP}
-    for i in range(3):
+    n_probe = 12 if calls_per_step * n_layers <= 4 else 3       # short steps: the first few are not representative
+    for i in range(n_probe):
         step(i, probe)
     torch.cuda.synchronize()
-    dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 3:]))
+    dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 2:]))
 
     for i in range(args.warmup):
         step(i)
