@@ -465,19 +465,24 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   // The DMA is issued through inline assembly on purpose: the compiler then neither orders later LDS
   // reads behind it (it would drain every outstanding load before each fragment read) nor counts it in
   // its own vmcnt bookkeeping; arrival is awaited by hand (s_waitcnt vmcnt) ahead of the barriers.
-  auto dma16 = [&](const char* tile_base, uint32_t byte_off, const char* lds_dst) {
-    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(const __attribute__((address_space(3))) char*)lds_dst);
+  // LDS destinations are handled as integers (LDS address of smem + byte offset, all scalar): a generic pointer
+  // would drag a null check and 64-bit arithmetic into every request.  wave_rows: where this wave's rows start
+  // inside a tile, as a scalar of its own; the row and mask arithmetic above keeps the per-lane `wave`.
+  const uint32_t smem_at = (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)smem;
+  const uint32_t wave_rows = __builtin_amdgcn_readfirstlane((uint32_t)(2 * wave * 1024));
+  auto dma16 = [&](const char* tile_base, uint32_t byte_off, uint32_t lds_off) {  // lds_off: byte offset into smem
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(smem_at + lds_off);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(m0v), "v"(byte_off), "s"(tile_base)
                  : "memory", "m0");
   };
-  auto dma_tile = [&](const char* base, int j, char* slot, const uint32_t (&goff)[2], bool is_v) {
+  auto dma_tile = [&](const char* base, int j, uint32_t slot, const uint32_t (&goff)[2], bool is_v) {
     const int k0 = j * BK;
     const char* tp = base + (size_t)k0 * (D * 2);
     if (kv_begin + k0 + BK <= a.m) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) dma16(tp, goff[i], slot + (2 * wave + i) * 1024);
+      for (int i = 0; i < 2; ++i) dma16(tp, goff[i], slot + wave_rows + i * 1024);
     } else {
       // last tile of the cache: rows past the final key re-read that key (their scores are masked)
       const int last = a.m - 1 - kv_begin - k0;
@@ -486,12 +491,14 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
         const int row = grow[i], pos = lane & 15;
         const int src_chunk = is_v ? (pos ^ (4 * (row & 3))) : (pos ^ (row & 15));
         const uint32_t off = (uint32_t)(min(row, last) * (D * 2) + src_chunk * 16);
-        dma16(tp, off, slot + (2 * wave + i) * 1024);
+        dma16(tp, off, slot + wave_rows + i * 1024);
       }
     }
   };
   auto kslot = [&](int j) { return smem + (j % NSLOT) * TILE; };
   auto vslot = [&](int j) { return smem + (NSLOT + j % NSLOT) * TILE; };
+  auto kslot_off = [&](int j) { return (uint32_t)((j % NSLOT) * TILE); };  // the same as byte offsets, for the requests
+  auto vslot_off = [&](int j) { return (uint32_t)((NSLOT + j % NSLOT) * TILE); };
 
   // ---- read side: per-lane swizzled byte offsets inside a slot
   uint32_t kaddr[ND], vaddr[NV];
@@ -592,11 +599,11 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   };
 
   // ---- prologue: K(0), V(0), K(1) must have landed; V(1), K(2) stay in flight
-  dma_tile(kbase, 0, kslot(0), goff_k, false);
-  dma_tile(vbase, 0, vslot(0), goff_v, true);
-  if (n_tiles > 1) dma_tile(kbase, 1, kslot(1), goff_k, false);
-  if (n_tiles > 1) dma_tile(vbase, 1, vslot(1), goff_v, true);
-  if (n_tiles > 2) dma_tile(kbase, 2, kslot(2), goff_k, false);
+  dma_tile(kbase, 0, kslot_off(0), goff_k, false);
+  dma_tile(vbase, 0, vslot_off(0), goff_v, true);
+  if (n_tiles > 1) dma_tile(kbase, 1, kslot_off(1), goff_k, false);
+  if (n_tiles > 1) dma_tile(vbase, 1, vslot_off(1), goff_v, true);
+  if (n_tiles > 2) dma_tile(kbase, 2, kslot_off(2), goff_k, false);
   if (n_tiles > 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);        // vmcnt(4): everything but V(1), K(2)
   else if (n_tiles > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);   // vmcnt(2): everything but V(1)
   else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
@@ -618,8 +625,8 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   // step `tile`: S(tile) is in sc; computes S(tile + 1) into sn and adds tile's V contribution
   auto step = [&](int tile, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     const bool more_k = tile + 3 < n_tiles, more_v = tile + 2 < n_tiles;
-    if (more_k) dma_tile(kbase, tile + 3, kslot(tile + 3), goff_k, false);
-    if (more_v) dma_tile(vbase, tile + 2, vslot(tile + 2), goff_v, true);
+    if (more_k) dma_tile(kbase, tile + 3, kslot_off(tile + 3), goff_k, false);
+    if (more_v) dma_tile(vbase, tile + 2, vslot_off(tile + 2), goff_v, true);
     const char* k_next = kslot(tile + 1);
     const char* v_cur = vslot(tile);
     if (tile < n_full) {
