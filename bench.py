@@ -159,6 +159,13 @@ def measured_peaks(samkv, iters=7):
         flop, ms = timed(lambda: samkv.samkv_peak_mfma_bf16(sink, n_cu * wps, 4000 // wps))
         out[f"mfma_bf16_tflops_{wps}_waves_per_simd"] = round(flop / ms / 1e9, 1)
     out["mfma_bf16_tflops"] = max(v for k, v in out.items() if k.startswith("mfma"))
+    # the same loop with pseudo-random operands (full mantissas): the device keeps inside its power limit by lowering
+    # the clock, and real data toggle far more bits than small integers do.  Sustained figure: launches back to back
+    # for about a quarter of a second before the timed ones.
+    for _ in range(40):
+        samkv.samkv_peak_mfma_bf16_data(sink, n_cu * 4, 1000, 2)
+    flop, ms = timed(lambda: samkv.samkv_peak_mfma_bf16_data(sink, n_cu * 4, 1000, 2))
+    out["mfma_bf16_tflops_random_operands"] = round(flop / ms / 1e9, 1)
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty_like(src)
     nbytes, ms = timed(lambda: samkv.samkv_peak_copy(src, dst))
@@ -390,8 +397,9 @@ def main() -> int:
     # below carries them only around that one call)
     probe = {name: [] for name in STEP}
     n_probe = 12 if calls_per_step * n_layers <= 4 else 3       # short steps: the first few are not representative
-    for i in range(n_probe):
-        step(i, probe)
+    for name in STEP:                                           # one call bracketed at a time, as in the timed region
+        for i in range(n_probe):
+            step(i, probe, only=name)
     torch.cuda.synchronize()
     dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 2:]))
 
@@ -467,7 +475,10 @@ def main() -> int:
     work = algorithmic_work(w, w.lens, m, w.n_q_tok)
     per_kernel = {}
     for name in STEP + tuple(n for n in KERNELS + EXTRA if n not in STEP):
-        ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
+        # the dominant call: mean over the timed region; the others: median of the untimed pass, whose first call of a
+        # kernel pays for loading it and which an occasional host hiccup of tens of milliseconds would distort
+        samples = [a.elapsed_time(b) for a, b in events[name]]
+        ms = float(np.mean(samples) if name == dom else np.median(samples))
         gbs = work[name]["bytes"] * layers_per_call / (ms * 1e-3) / 1e9
         tfl = work[name]["flops"] * layers_per_call / (ms * 1e-3) / 1e12
         per_kernel[name] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
@@ -517,6 +528,7 @@ def main() -> int:
         out["measured_peaks"] = mp
         if roof["bound"] == "mfma":
             roof["frac_of_measured_peak"] = round(roof["achieved"] / mp["mfma_bf16_tflops"], 4)
+            roof["frac_of_measured_peak_random_operands"] = round(roof["achieved"] / mp["mfma_bf16_tflops_random_operands"], 4)
         elif roof["bound"] == "hbm":
             roof["frac_of_measured_peak"] = round(roof["achieved"] / mp["read_gbs"], 4)
     if two_ms is not None:

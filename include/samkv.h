@@ -297,6 +297,11 @@ int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, 
  *   samkv_peak_copy       dst[0..bytes) = src[0..bytes), 16-byte aligned, bytes a multiple of 16.
  *   samkv_peak_read       reads src[0..bytes) once (16-byte aligned, a multiple of 16); sink: 4 bytes, untouched. */
 int samkv_peak_mfma_bf16(float* sink, int32_t n_blocks, int32_t iters, void* stream);
+/* The same loop with a chosen operand pattern: 0 small integers (what samkv_peak_mfma_bf16 uses), 1 zeros, 2
+ * pseudo-random values with full mantissas.  The sustained rate depends on it: the device holds its power limit by
+ * lowering the clock, and the matrix unit draws more the more operand bits toggle.  Pattern 2 is the ceiling for a
+ * kernel that multiplies real data.  Other patterns: SAMKV_EINVAL. */
+int samkv_peak_mfma_bf16_data(float* sink, int32_t n_blocks, int32_t iters, int32_t pattern, void* stream);
 int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream);
 int samkv_peak_read(const void* src, size_t bytes, void* sink, void* stream);
 

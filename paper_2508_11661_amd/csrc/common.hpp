@@ -74,7 +74,7 @@ hipError_t launch_filter_expand(const int32_t* sel, const int32_t* bidx, const I
                                 int n_ctx, int hkv, int n_sel, int m_total, int block, int32_t* start, int32_t* tok_off,
                                 int32_t* gidx, hipStream_t s);
 
-hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, hipStream_t s);
+hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, int pattern, hipStream_t s);
 hipError_t launch_peak_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_peak_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 

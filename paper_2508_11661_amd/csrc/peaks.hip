@@ -10,13 +10,32 @@
 namespace samkv {
 namespace {
 
-__global__ __launch_bounds__(256) void k_peak_mfma(float* sink, int iters) {
-  bf16x8 a, b;
+// operand pattern: 0 small integers (a few mantissa bits set), 1 zeros, 2 pseudo-random values in [-2, 2) with full
+// mantissas.  The pattern matters: the matrix unit's power grows with the number of bits that toggle, and under
+// sustained load the device lowers its clock to stay inside its power limit, so the rate with realistic operands
+// (2) is the ceiling a kernel that multiplies real data can be measured against.
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(256) void k_peak_mfma(float* sink, int iters, int pattern) {
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
-    b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
-  }
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float fa = 0.f, fb = 0.f;
+      if (pattern == 0) {
+        fa = (float)((threadIdx.x + e) & 3);
+        fb = (float)((threadIdx.x * 3 + e) & 1);
+      } else if (pattern == 2) {
+        fa = ((int)(mix32(threadIdx.x * 64 + v * 8 + e + 1) & 0xFFFF) - 32768) / 16384.f;
+        fb = ((int)(mix32(threadIdx.x * 64 + v * 8 + e + 7777) & 0xFFFF) - 32768) / 16384.f;
+      }
+      a[v][e] = (__bf16)fa;
+      b[v][e] = (__bf16)fb;
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -26,14 +45,14 @@ __global__ __launch_bounds__(256) void k_peak_mfma(float* sink, int iters) {
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + i) & 3], b[u], acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 16; ++j) s += acc[i][j];
-  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; never true for these operands
+  if (s == 12345.678f) sink[0] = s;  // keeps the loop alive; practically never true
 }
 
 __global__ __launch_bounds__(256) void k_peak_copy(const u32x4* src, u32x4* dst, size_t n16) {
@@ -82,8 +101,8 @@ hipError_t launch_peak_read(const void* src, size_t bytes, uint32_t* sink, hipSt
 }
 
 // flop of one launch: n_blocks * 4 waves * iters * 16 instructions * 32768
-hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, hipStream_t s) {
-  hipLaunchKernelGGL(k_peak_mfma, dim3(n_blocks), dim3(256), 0, s, sink, iters);
+hipError_t launch_peak_mfma(float* sink, int n_blocks, int iters, int pattern, hipStream_t s) {
+  hipLaunchKernelGGL(k_peak_mfma, dim3(n_blocks), dim3(256), 0, s, sink, iters, pattern);
   return hipGetLastError();
 }
 

@@ -617,8 +617,12 @@ int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, con
 }
 
 int samkv_peak_mfma_bf16(float* sink, int32_t n_blocks, int32_t iters, void* stream) {
-  if (sink == nullptr || n_blocks < 1 || n_blocks > (1 << 20) || iters < 1) return SAMKV_EINVAL;
-  return dev(launch_peak_mfma(sink, n_blocks, iters, static_cast<hipStream_t>(stream)));
+  return samkv_peak_mfma_bf16_data(sink, n_blocks, iters, 0, stream);
+}
+
+int samkv_peak_mfma_bf16_data(float* sink, int32_t n_blocks, int32_t iters, int32_t pattern, void* stream) {
+  if (sink == nullptr || n_blocks < 1 || n_blocks > (1 << 20) || iters < 1 || pattern < 0 || pattern > 2) return SAMKV_EINVAL;
+  return dev(launch_peak_mfma(sink, n_blocks, iters, pattern, static_cast<hipStream_t>(stream)));
 }
 
 int samkv_peak_copy(const void* src, void* dst, size_t bytes, void* stream) {

@@ -22,7 +22,7 @@ EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
-           "samkv_kv_update", "samkv_peak_mfma_bf16", "samkv_peak_copy", "samkv_peak_read")
+           "samkv_kv_update", "samkv_peak_mfma_bf16", "samkv_peak_mfma_bf16_data", "samkv_peak_copy", "samkv_peak_read")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
 
@@ -94,6 +94,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_query_attn_self.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_peak_mfma_bf16.restype = ctypes.c_int
     lib.samkv_peak_mfma_bf16.argtypes = [vp, i32, i32, vp]
+    lib.samkv_peak_mfma_bf16_data.restype = ctypes.c_int
+    lib.samkv_peak_mfma_bf16_data.argtypes = [vp, i32, i32, i32, vp]
     lib.samkv_peak_copy.restype = ctypes.c_int
     lib.samkv_peak_copy.argtypes = [vp, vp, sz, vp]
     lib.samkv_peak_read.restype = ctypes.c_int
@@ -175,6 +177,12 @@ class Caches:
 def samkv_peak_mfma_bf16(sink: torch.Tensor, n_blocks: int, iters: int) -> int:
     """Launches the pure-MFMA micro-kernel; returns the flop of the launch."""
     _check(_lib.samkv_peak_mfma_bf16(_ptr(sink), n_blocks, iters, _stream()), "samkv_peak_mfma_bf16")
+    return n_blocks * 4 * iters * 16 * 32768
+
+
+def samkv_peak_mfma_bf16_data(sink: torch.Tensor, n_blocks: int, iters: int, pattern: int) -> int:
+    """The same with an operand pattern (0 small integers, 1 zeros, 2 random full mantissas); returns the flop."""
+    _check(_lib.samkv_peak_mfma_bf16_data(_ptr(sink), n_blocks, iters, pattern, _stream()), "samkv_peak_mfma_bf16_data")
     return n_blocks * 4 * iters * 16 * 32768
 
 

@@ -182,6 +182,11 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_kv_update(fake, fake, fake, fake, 8, 2, 128, 1, 2, None) == -1
     assert L.samkv_kv_update(fake, fake, fake, fake, 8, 2, 96, 1, 1, None) == -2
     assert L.samkv_kv_update(fake, fake, fake, fake, 8, 2, 128, 3, 1, None) == -2
+    # the measuring kernels
+    assert L.samkv_peak_mfma_bf16(None, 4, 4, None) == -1
+    assert L.samkv_peak_mfma_bf16_data(fake, 4, 4, 3, None) == -1     # unknown operand pattern
+    assert L.samkv_peak_mfma_bf16_data(fake, 0, 4, 2, None) == -1
+    assert L.samkv_peak_copy(fake, fake, 24, None) == -1               # not a multiple of 16
     assert S._lib.samkv_strerror(-3).decode().startswith("workspace")
 
 
