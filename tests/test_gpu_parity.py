@@ -565,3 +565,22 @@ def test_layers_stacked_as_heads(S):
         H.check_attention(buf.rec_out[gh].cpu().numpy(), buf.rec_lse[gh].cpu().numpy(), o_ref, l_ref, "bf16", f"layer {l} recompute")
         o_ref, l_ref = O.attention(x.q_tok[heads], ref.k_c[clean], ref.v_c[clean], scale, False)
         H.check_attention(buf.q_out[gh].cpu().numpy(), buf.q_lse[gh].cpu().numpy(), o_ref, l_ref, "bf16", f"layer {l} query")
+
+
+def test_measuring_kernels_run_and_leave_their_sink_alone(S):
+    """The micro-kernels that bench.py quotes ceilings from: the copy copies, the others touch nothing."""
+    import torch
+    sink = torch.full((4,), 7.0, device="cuda")
+    for pattern in (0, 1, 2):
+        assert S.samkv_peak_mfma_bf16_data(sink, 8, 4, pattern) == 8 * 4 * 4 * 16 * 32768
+    assert S.samkv_peak_mfma_bf16(sink, 8, 4) == 8 * 4 * 4 * 16 * 32768
+    src = torch.arange(1 << 16, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    assert S.samkv_peak_copy(src, dst) == 2 * src.numel() * 4
+    assert S.samkv_peak_read(src, sink) == src.numel() * 4
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert torch.equal(sink.cpu(), torch.full((4,), 7.0))
+    with pytest.raises(S.SamKVError):
+        S.samkv_peak_mfma_bf16_data(sink, 8, 4, 5)
+
