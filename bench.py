@@ -239,6 +239,26 @@ def at_scale(samkv, iters=5):
     res["score_select_fused"] = {"ms": round(ms, 4), "GB/s": round(ss_bytes / ms / 1e6, 1),
                                  "frac_hbm": round(ss_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
+    # the causal attention once more on all-zero operands: same instruction stream, far fewer bits toggling.  The
+    # difference to the figure above is what the device's power limit costs on real data.
+    zq, zk, zv = torch.zeros_like(q_rec), torch.zeros_like(buf.k_c), torch.zeros_like(buf.v_c)
+    zcall = lambda: samkv.samkv_recompute_attn(zq, zk, zv, scale, buf.rec_out, buf.rec_lse, buf.ws)
+    zcall()
+    torch.cuda.synchronize()
+    ev = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        zcall()
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
+    res["recompute_attn_zero_operands"] = {"ms": round(ms, 4),
+                                           "TFLOP/s": round(work["recompute_attn"]["flops"] / ms / 1e9, 1),
+                                           "note": "same launch on all-zero Q, K, V: not power-limited"}
+    del zq, zk, zv
+
     # block-level variant of the selection (64-token blocks, 1 initial + 2 local blocks forced, per-document share
     # 0.15 of the middle blocks), with and without the cross-document filter, and the gather that follows each
     block, p = 64, [0.15] * w.n_ctx
