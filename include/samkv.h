@@ -31,8 +31,11 @@
  *   - Return value: SAMKV_OK or a negative error.  Argument errors are found before anything is
  *     launched and leave the outputs untouched.  Results are deterministic (no float atomics).
  *   - HIP graphs: every call only enqueues kernels (no memsets, no copies, no allocation), so a sequence of calls
- *     can be captured.  The first attention call of a process raises the dynamic-LDS limit of its kernel with
- *     hipFuncSetAttribute; make one call of each attention entry point before capturing.
+ *     can be captured.  The first attention call on a device raises the dynamic-LDS limit of every attention kernel
+ *     variant with hipFuncSetAttribute; make one attention call (any shape) before capturing.
+ *   - Alignment: every K, V and Q tensor, the compacted caches and the attention outputs must be 16-byte aligned
+ *     (rows are moved with 16-byte accesses); scores, positions and log-sum-exp 4-byte aligned.  Anything else is
+ *     SAMKV_EINVAL, found before any launch.
  *   - Limits: head_dim in {64, 128}; n_ctx <= SAMKV_MAX_CTX; each document at most SAMKV_MAX_LEN
  *     tokens; n_q_heads a multiple of n_kv_heads.
  */
@@ -250,8 +253,12 @@ int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, con
  *   out[h][p][:] = sum_{j <= p} softmax_j(scale * <q_rec[h][p], k_c[g][j]>) * v_c[g][j]
  *   lse[h][p]    = log sum_{j <= p} exp(scale * <q_rec[h][p], k_c[g][j]>)
  *   q_rec [Hq][M][d], k_c, v_c [Hkv][M][d] in `dtype`; out [Hq][M][d], lse [Hq][M] float32.
- * bf16: products on the bf16 matrix cores, softmax statistics and accumulators float32, the
- * softmax weights are rounded to bf16 before they multiply V.  f32: float32 throughout. */
+ * bf16: scores on the bf16 matrix cores, softmax statistics and accumulators float32.  The second product runs on
+ * the half-precision matrix cores: the softmax weights are rounded to IEEE half precision (11-bit significand), and
+ * V is first rewritten into the workspace as half precision, each KV head scaled by a power of two so that nothing
+ * overflows and bf16 values down to 2^-32 of the head's largest magnitude stay exact (smaller ones lose at most
+ * 2^-40 of that magnitude).  f32: float32 throughout.
+ * ws: samkv_workspace_bytes(...) bytes, 256-byte aligned, for bf16 (SAMKV_EWORKSPACE otherwise); f32 needs none. */
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total,
                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
                          float scale, float* out, float* lse, void* ws, size_t ws_bytes, void* stream);

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libsamkv.so")
-SOURCES = ["samkv_api.hip", "score.hip", "select.hip", "fused.hip", "block.hip", "gather.hip", "attn.hip", "update.hip", "peaks.hip"]
+SOURCES = ["samkv_api.hip", "score.hip", "select.hip", "fused.hip", "block.hip", "gather.hip", "attn.hip", "vprep.hip", "update.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

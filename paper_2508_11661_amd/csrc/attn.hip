@@ -9,14 +9,19 @@
 //                 loaded once).  Computing the transpose puts one query row in one lane column, so the
 //                 softmax weights come out of the accumulator already in the B-operand layout of the
 //                 next product and never travel through LDS.
-//   O^T += V^T P^T  same instruction, A = V^T read from the row-major V tile in LDS with the
-//                 transposing LDS read (ds_read_b64_tr_b16), B = P^T (bf16) from registers.
+//   O^T += V^T P^T  v_mfma_f32_32x32x16_f16, A = V^T read from the row-major V tile in LDS with the
+//                 transposing LDS read (ds_read_b64_tr_b16), B = P^T from registers.  Both operands are IEEE
+//                 half precision: the weights keep an 11-bit significand (bf16 weights would cost 2^-9 of the
+//                 spread of V per output), and V arrives as the scaled half-precision copy of vprep.hip, whose
+//                 power-of-two scale the final normalisation undoes.
 //   K/V tiles are double-buffered in LDS; the next tile's global loads are issued before the current
 //   tile's math and land in LDS after it, one barrier per tile.
 // f32 kernel (k_attn_f32): plain FMA arithmetic for float32 caches, 16 rows per workgroup.
 // Keys can be cut into chunks (not causal only); k_attn_merge combines the per-chunk results with
 // their log-sum-exp.
 #include <math.h>
+
+#include <mutex>
 
 #include "common.hpp"
 
@@ -26,7 +31,8 @@ namespace {
 struct AttnArgs {
   const void* q;
   const void* k;
-  const void* v;
+  const void* v;           // half-precision copy of V (bf16 kernels)
+  const float* v_unscale;  // per KV head: undoes the copy's scale
   float* out;
   float* lse;
   float* part_o;
@@ -278,21 +284,21 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) s[kb][j] = __builtin_amdgcn_exp2f(fmaf(s[kb][j], c2, -m_use));
-      // weights go to bf16 for the second product; their row sum is taken over the ROUNDED weights
-      // (bf16 pair . (1,1) accumulated in float32), so numerator and denominator see the same weights
-      bf16x8 bp[2][2];
+      // weights go to half precision for the second product; their row sum is taken over the ROUNDED weights
+      // (pair . (1,1) accumulated in float32), so numerator and denominator see the same weights
+      f16x8 bp[2][2];
       float psum = 0.f;
-      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+      const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
           for (int e = 0; e < 8; e += 2) {
-            bf16x2 pr = {(__bf16)s[kb][8 * s2 + e], (__bf16)s[kb][8 * s2 + e + 1]};
+            f16x2 pr = {(_Float16)s[kb][8 * s2 + e], (_Float16)s[kb][8 * s2 + e + 1]};
             bp[kb][s2][e] = pr[0];
             bp[kb][s2][e + 1] = pr[1];
-            psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+            psum = __builtin_amdgcn_fdot2(pr, ones, psum, false);
           }
       l_run = fmaf(l_run, alpha, psum);
       if (__any(alpha != 1.f)) {
@@ -312,10 +318,10 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
             const char* vp = sv + key1 * C::VSTR + (dvb * 32 + q2 * 16 + 4 * (i16 & 3)) * 2;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * C::VSTR));
-            union { struct { s16x4 lo, hi; } s; bf16x8 v; } av;
+            union { struct { s16x4 lo, hi; } s; f16x8 v; } av;
             av.s.lo = lo;
             av.s.hi = hi;
-            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
+            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
           }
         }
     }
@@ -350,7 +356,7 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
   }
 
   const float l_tot = sum_across_halves(l_run);
-  const float inv = 1.f / l_tot;
+  const float inv = a.v_unscale[kvh] / l_tot;
   const size_t row0 = (size_t)batch * a.rows + wave_first;
   float* op0;
   float* lp0;
@@ -397,7 +403,7 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
 //     To keep that block free of branches a wave splits its tiles into `n_full` unmasked tiles (this
 //     path) and at most one tail tile (the causal diagonal or the ragged end; plain path with masks),
 //     and the running maximum is only raised when a row outgrows it by more than 2^8 ("lazy rescale"):
-//     weights then stay below 256, which float32 sums and bf16 weights hold without loss, and the
+//     weights then stay below 256, which float32 sums and half-precision weights hold without loss, and the
 //     rescale of O becomes a rare side branch ahead of the block.
 // (2) Asynchronous tile loads.  K/V tiles travel from global memory straight into LDS
 //     (global_load_lds_dwordx4: no staging registers, no LDS store instructions) into a ring of three K
@@ -550,13 +556,13 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
     for (int dc = 0; dc < ND; ++dc) ak[dc] = *reinterpret_cast<const bf16x8*>(ks + kaddr[dc] + kb * 32 * 256);
   };
   // V^T fragments of key group g (16 keys) for the NV blocks of O^T: two transposing reads each
-  auto vfrags = [&](const char* vs, int g, bf16x8 (&av)[NV]) {
+  auto vfrags = [&](const char* vs, int g, f16x8 (&av)[NV]) {
 #pragma unroll
     for (int dvb = 0; dvb < NV; ++dvb) {
       const char* vp = vs + vaddr[dvb] + g * 16 * 256;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
       const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * 256));
-      union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
+      union { struct { s16x4 lo, hi; } s; f16x8 v; } u;
       u.s.lo = lo;
       u.s.hi = hi;
       av[dvb] = u.v;
@@ -566,12 +572,12 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   // i.e. one group of products ahead of its use, instead of right in front of it
   constexpr int kHoldLds = 0x47F;
   auto weights_pv = [&](f32x16 (&s)[2], const char* vs, float m_use) {
-    bf16x8 bp[2][2];
-    bf16x8 va[2][NV];
+    f16x8 bp[2][2];
+    f16x8 va[2][NV];
     vfrags(vs, 0, va[0]);  // lands while the weights are computed
     __builtin_amdgcn_sched_barrier(kHoldLds);
     float psum = 0.f;
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -580,10 +586,10 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
         for (int e = 0; e < 8; e += 2) {
           const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * s2 + e], c2, -m_use));
           const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * s2 + e + 1], c2, -m_use));
-          bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+          f16x2 pr = {(_Float16)p0, (_Float16)p1};
           bp[kb][s2][e] = pr[0];
           bp[kb][s2][e + 1] = pr[1];
-          psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+          psum = __builtin_amdgcn_fdot2(pr, ones, psum, false);
         }
     l_run += psum;
 #pragma unroll
@@ -594,7 +600,7 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
       }
 #pragma unroll
       for (int dvb = 0; dvb < NV; ++dvb)
-        o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[g & 1][dvb], bp[g >> 1][g & 1], o[dvb], 0, 0, 0);
+        o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[g & 1][dvb], bp[g >> 1][g & 1], o[dvb], 0, 0, 0);
     }
   };
 
@@ -665,7 +671,7 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   }
 
   const float l_tot = sum_across_halves(l_run);
-  const float inv = 1.f / l_tot;
+  const float inv = a.v_unscale[kvh] / l_tot;
   const size_t row0 = (size_t)batch * a.rows + wave_first;
   float* op0;
   float* lp0;
@@ -819,7 +825,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a, int d) {
 
 AttnArgs make_args(const AttnLaunch& l) {
   AttnArgs a;
-  a.q = l.q; a.k = l.k; a.v = l.v; a.out = l.out; a.lse = l.lse;
+  a.q = l.q; a.k = l.k; a.v = l.v; a.v_unscale = l.v_unscale; a.out = l.out; a.lse = l.lse;
   a.part_o = l.part_o; a.part_lse = l.part_lse;
   a.rows = l.rows; a.m = l.m; a.batch_per_kv = l.batch_per_kv; a.n_batch = l.n_batch;
   a.n_split = l.causal ? 1 : l.n_split;
@@ -839,16 +845,17 @@ dim3 attn_grid(AttnArgs* a, int tiles) {
   return dim3(a->n_batch, tiles, a->n_split);
 }
 
+constexpr int kDmaLdsBytes = 6 * 64 * 256;
+
+template <int D, bool CAUSAL, int NW, int KG = 1>
+hipError_t raise_lds_limit() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, Bf16Cfg<D, NW, KG>::LDS_BYTES);
+}
+
 template <int D, bool CAUSAL, int NW, int KG = 1>
 hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
   using C = Bf16Cfg<D, NW, KG>;
-  static bool attr_set = false;  // per process; the attribute belongs to the function, not the stream
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   AttnArgs a = make_args(l);
   dim3 grid = attn_grid(&a, (l.rows + C::BQ - 1) / C::BQ);
   hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW, KG>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
@@ -857,14 +864,7 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
 
 template <bool CAUSAL>
 hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
-  constexpr int LDS = 6 * 64 * 256;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<CAUSAL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr int LDS = kDmaLdsBytes;
   AttnArgs a = make_args(l);
   dim3 grid = attn_grid(&a, (l.rows + 255) / 256);
   hipLaunchKernelGGL((k_attn_bf16_dma<CAUSAL>), grid, dim3(512), LDS, s, a);
@@ -896,7 +896,37 @@ hipError_t run_f32(const AttnLaunch& l, hipStream_t s) {
 
 }  // namespace
 
+// Every bf16 attention kernel uses more dynamic LDS than the default limit allows; the limit belongs to the function
+// on a device, so it is raised for ALL variants the first time any attention call runs on that device.  After that
+// no attention call touches anything but the stream, whatever variant its shape selects (HIP graph capture).
+hipError_t attn_prepare_device() {
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static bool done[kMaxDev] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (done[dev]) return hipSuccess;
+  const hipError_t all[] = {
+      raise_lds_limit<128, true, 8>(),     raise_lds_limit<128, false, 8>(), raise_lds_limit<128, true, 4>(),
+      raise_lds_limit<128, false, 4>(),    raise_lds_limit<128, true, 8, 2>(), raise_lds_limit<64, true, 8>(),
+      raise_lds_limit<64, false, 8>(),     raise_lds_limit<64, true, 4>(),   raise_lds_limit<64, false, 4>(),
+      raise_lds_limit<64, true, 8, 2>(),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<false>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes)};
+  for (hipError_t x : all)
+    if (x != hipSuccess) return x;
+  done[dev] = true;
+  return hipSuccess;
+}
+
 hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
+  const hipError_t e = attn_prepare_device();
+  if (e != hipSuccess) return e;
   if (l.d == 128) return l.causal ? run_bf16_nw<128, true>(l, s) : run_bf16_nw<128, false>(l, s);
   return l.causal ? run_bf16_nw<64, true>(l, s) : run_bf16_nw<64, false>(l, s);
 }

@@ -21,6 +21,8 @@ struct IntTable {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -113,7 +115,8 @@ struct AttnLaunch {
   int n_batch, batch_per_kv, rows, m;
   const void* q;   // [n_batch][rows][d]
   const void* k;   // [n_batch / batch_per_kv][m][d]
-  const void* v;
+  const void* v;   // bf16 kernels: the half-precision copy that launch_v_prep wrote; f32 kernel: V itself
+  const float* v_unscale;  // bf16 kernels: [n_batch / batch_per_kv] factor that undoes the copy's power-of-two scale
   float* out;      // [n_batch][rows][d]
   float* lse;      // [n_batch][rows]
   float scale;
@@ -124,6 +127,14 @@ struct AttnLaunch {
 hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnLaunch& a, hipStream_t s);
+
+// Half-precision copy of a bf16 V tensor [n_kv][m][d] for the attention kernels, one power-of-two scale per KV head.
+// part: [n_kv][v_prep_chunks(n_kv, m)] scratch words; unscale: [n_kv] factors that undo the scale.
+int v_prep_chunks(int n_kv, int m);
+hipError_t launch_v_prep(const void* v, int n_kv, int m, int d, void* v16, uint32_t* part, float* unscale, hipStream_t s);
+
+// Raises the dynamic-LDS limit of every bf16 attention kernel variant on the current device (once per device).
+hipError_t attn_prepare_device();
 
 // Cache update after recomputation: rows of `cur` (old, updated in place) against rows of `fresh` (new).
 struct UpdateLaunch {

@@ -12,6 +12,8 @@ namespace {
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+// every kernel moves tensor rows with 16-byte vector accesses
+bool aligned16(const void* p) { return ((uintptr_t)p % 16) == 0; }
 
 int kept_count(int len, float ratio) {
   if (len < 1 || !(ratio > 0.f) || ratio > 1.f) return 0;
@@ -42,6 +44,7 @@ int check_caches(const samkv_caches* c, bool need_k, bool need_v, Shape* s) {
     if (c->len[i] < 1) return SAMKV_EINVAL;
     if (c->len[i] > SAMKV_MAX_LEN) return SAMKV_EUNSUPPORTED;
     if ((need_k && c->k[i] == nullptr) || (need_v && c->v[i] == nullptr)) return SAMKV_EINVAL;
+    if ((need_k && !aligned16(c->k[i])) || (need_v && !aligned16(c->v[i]))) return SAMKV_EINVAL;
     total += c->len[i];
     if (total > 0x7FFFFFFF / 2) return SAMKV_EUNSUPPORTED;
     s->cu_len.v[i + 1] = (int32_t)total;
@@ -128,6 +131,43 @@ SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
   return p;
 }
 
+// bf16 attention: the half-precision copy of V [Hkv][M][d], the per-chunk maxima and the per-head unscale factors.
+struct VPrepWs { size_t v16, part, unscale, bytes; };
+VPrepWs vprep_ws(int dtype, int hkv, int m, int d) {
+  VPrepWs w;
+  w.v16 = w.part = w.unscale = w.bytes = 0;
+  if (dtype != SAMKV_BF16) return w;
+  w.part = align_up((size_t)hkv * m * d * 2);
+  w.unscale = align_up(w.part + (size_t)hkv * v_prep_chunks(hkv, m) * 4);
+  w.bytes = align_up(w.unscale + (size_t)hkv * 4);
+  return w;
+}
+
+// Workspace of one attention problem: the key-chunk partials (not causal only), then the V preparation.
+struct AttnWs { SplitPlan split; VPrepWs vp; size_t vp_at, bytes; };
+AttnWs attn_ws(int dtype, bool causal, int hkv, int rows_per_kv, int m, int d) {
+  AttnWs w;
+  if (causal) {
+    w.split.n_split = 1; w.split.chunk = m; w.split.part_o = w.split.part_lse = w.split.bytes = 0;
+  } else {
+    w.split = plan_splits(dtype, hkv, rows_per_kv, m, d);
+  }
+  w.vp = vprep_ws(dtype, hkv, m, d);
+  w.vp_at = w.split.bytes;
+  w.bytes = w.vp_at + w.vp.bytes;
+  return w;
+}
+
+// Runs the V preparation of a bf16 attention call into its workspace slice and points the launch at the copy.
+hipError_t prepare_v(AttnLaunch* a, const VPrepWs& vp, char* at, int hkv, hipStream_t s) {
+  if (a->dtype != SAMKV_BF16) return hipSuccess;
+  float* unscale = reinterpret_cast<float*>(at + vp.unscale);
+  const hipError_t e = launch_v_prep(a->v, hkv, a->m, a->d, at + vp.v16, reinterpret_cast<uint32_t*>(at + vp.part), unscale, s);
+  a->v = at + vp.v16;
+  a->v_unscale = unscale;
+  return e;
+}
+
 // Workspace of samkv_query_attn_self: two result slots [2][Hq*Lq][d] + [2][Hq*Lq] (cache part, self part),
 // followed by whatever the cache part itself needs for its key chunks.
 struct SelfWs { size_t part_o, part_lse, inner, bytes; };
@@ -137,17 +177,22 @@ SelfWs self_ws(int hq, int hkv, int d, int n_q_tok, int m_total, int dtype) {
   w.part_o = 0;
   w.part_lse = align_up(2 * n_rows * d * 4);
   w.inner = align_up(w.part_lse + 2 * n_rows * 4);
-  w.bytes = w.inner + plan_splits(dtype, hkv, (hq / hkv) * n_q_tok, m_total, d).bytes;
+  // the two partial attentions run one after the other on the stream and share the inner region
+  const size_t cache_part = attn_ws(dtype, false, hkv, (hq / hkv) * n_q_tok, m_total, d).bytes;
+  const size_t self_part = attn_ws(dtype, true, hkv, 0, n_q_tok, d).bytes;
+  w.bytes = w.inner + (cache_part > self_part ? cache_part : self_part);
   return w;
 }
 
 int check_attn(const void* q, const void* k, const void* v, int rows, int m, int hq, int hkv, int d, int dtype,
                float scale, const float* out, const float* lse) {
   if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || lse == nullptr) return SAMKV_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || ((uintptr_t)lse % 4) != 0) return SAMKV_EINVAL;
   if (rows < 1 || m < 1 || hq < 1 || hkv < 1 || hq % hkv != 0 || !(scale > 0.f) || !isfinite(scale)) return SAMKV_EINVAL;
   if (dtype != SAMKV_F32 && dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
   if (d != 64 && d != 128) return SAMKV_EUNSUPPORTED;
-  if ((long long)hq * rows > 0x7FFFFFFF / 256 || m > 0x7FFFFFFF / 512 || rows / 16 > 65535) return SAMKV_EUNSUPPORTED;
+  if ((long long)hq * rows > 0x7FFFFFFF / 256 || m > 0x7FFFFFFF / 512 || rows / 16 > 65535 || hkv > 65535)
+    return SAMKV_EUNSUPPORTED;
   return SAMKV_OK;
 }
 
@@ -175,9 +220,11 @@ size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_head
   if (n_ctx < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_q_tok < 1 || m_total < 1) return 0;
   const size_t a = score_ws(n_ctx, n_q_heads, n_kv_heads, head_dim).bytes;
   const int rows = (n_q_heads / n_kv_heads) * n_q_tok;
-  size_t b = plan_splits(SAMKV_BF16, n_kv_heads, rows, m_total, head_dim).bytes;
-  const size_t c = plan_splits(SAMKV_F32, n_kv_heads, rows, m_total, head_dim).bytes;
+  size_t b = attn_ws(SAMKV_BF16, false, n_kv_heads, rows, m_total, head_dim).bytes;
+  const size_t c = attn_ws(SAMKV_F32, false, n_kv_heads, rows, m_total, head_dim).bytes;
   if (c > b) b = c;
+  const size_t r = attn_ws(SAMKV_BF16, true, n_kv_heads, 0, m_total, head_dim).bytes;
+  if (r > b) b = r;
   const size_t e = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, SAMKV_BF16).bytes;
   const size_t f = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, SAMKV_F32).bytes;
   if (e > b) b = e;
@@ -190,6 +237,7 @@ static int score_setup(const samkv_caches* caches, const void* q_tok, int32_t n_
   int rc = check_caches(caches, true, false, s);
   if (rc != SAMKV_OK) return rc;
   if (q_tok == nullptr || n_q_tok < 1 || (q_loc != nullptr && w_loc < 1)) return SAMKV_EINVAL;
+  if (!aligned16(q_tok) || !aligned16(q_loc) || ((uintptr_t)scores % 4) != 0) return SAMKV_EINVAL;
   const ScoreWs w = score_ws(s->n_ctx, s->hq, s->hkv, s->d);
   if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
   memset(kt, 0, sizeof(*kt));
@@ -238,7 +286,7 @@ static int score_select_common(const samkv_caches* caches, const void* q_tok, in
     Shape s2;
     rc = check_caches(caches, true, true, &s2);  // V is read as well
     if (rc != SAMKV_OK) return rc;
-    if (k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
+    if (k_c == nullptr || v_c == nullptr || !aligned16(k_c) || !aligned16(v_c)) return SAMKV_EINVAL;
     memset(&vt, 0, sizeof(vt));
     for (int i = 0; i < s.n_ctx; ++i) vt.p[i] = caches->v[i];
     ga.n_ctx = s.n_ctx; ga.hkv = s.hkv; ga.row_bytes = s.d * (s.dtype == SAMKV_BF16 ? 2 : 4);
@@ -500,6 +548,7 @@ int samkv_gather_g(const samkv_caches* caches, const int32_t* gidx, int32_t m_to
   int rc = check_caches(caches, true, true, &s);
   if (rc != SAMKV_OK) return rc;
   if (gidx == nullptr || k_c == nullptr || v_c == nullptr || m_total < 1) return SAMKV_EINVAL;
+  if (!aligned16(k_c) || !aligned16(v_c)) return SAMKV_EINVAL;
   PtrTable kt, vt;
   memset(&kt, 0, sizeof(kt));
   memset(&vt, 0, sizeof(vt));
@@ -513,11 +562,11 @@ int samkv_gather_q_g(const samkv_caches* caches, const void* const* q_cache, con
   Shape s;
   int rc = check_caches(caches, false, false, &s);
   if (rc != SAMKV_OK) return rc;
-  if (q_cache == nullptr || gidx == nullptr || q_rec == nullptr || m_total < 1) return SAMKV_EINVAL;
+  if (q_cache == nullptr || gidx == nullptr || q_rec == nullptr || m_total < 1 || !aligned16(q_rec)) return SAMKV_EINVAL;
   PtrTable qt;
   memset(&qt, 0, sizeof(qt));
   for (int i = 0; i < s.n_ctx; ++i) {
-    if (q_cache[i] == nullptr) return SAMKV_EINVAL;
+    if (q_cache[i] == nullptr || !aligned16(q_cache[i])) return SAMKV_EINVAL;
     qt.p[i] = q_cache[i];
   }
   return dev(launch_gather_g(s.d * (s.dtype == SAMKV_BF16 ? 2 : 4), qt, nullptr, s.cu_len, s.n_ctx, s.hq, s.hq / s.hkv,
@@ -533,7 +582,7 @@ int samkv_gather_v(const samkv_caches* caches, const int32_t* idx, const int32_t
   Shape s;
   int rc = check_caches(caches, true, true, &s);
   if (rc != SAMKV_OK) return rc;
-  if (idx == nullptr || k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
+  if (idx == nullptr || k_c == nullptr || v_c == nullptr || !aligned16(k_c) || !aligned16(v_c)) return SAMKV_EINVAL;
   IntTable cu_k;
   rc = checked_cu_k(caches, s, cu_k_host, &cu_k);
   if (rc != SAMKV_OK) return rc;
@@ -544,7 +593,7 @@ int samkv_gather(const samkv_caches* caches, const int32_t* idx, float ratio, vo
   Shape s;
   int rc = check_caches(caches, true, true, &s);
   if (rc != SAMKV_OK) return rc;
-  if (idx == nullptr || k_c == nullptr || v_c == nullptr) return SAMKV_EINVAL;
+  if (idx == nullptr || k_c == nullptr || v_c == nullptr || !aligned16(k_c) || !aligned16(v_c)) return SAMKV_EINVAL;
   IntTable cu_k;
   rc = kept_table(caches, ratio, 0, 0, &cu_k);
   if (rc != SAMKV_OK) return rc;
@@ -581,7 +630,7 @@ static int gather_q_common(const samkv_caches* caches, const Shape& s, const Int
   PtrTable qt;
   memset(&qt, 0, sizeof(qt));
   for (int i = 0; i < s.n_ctx; ++i) {
-    if (q_cache[i] == nullptr) return SAMKV_EINVAL;
+    if (q_cache[i] == nullptr || !aligned16(q_cache[i])) return SAMKV_EINVAL;
     qt.p[i] = q_cache[i];
   }
   GatherLaunch a;
@@ -597,7 +646,7 @@ int samkv_gather_q(const samkv_caches* caches, const void* const* q_cache, const
   Shape s;
   int rc = check_caches(caches, false, false, &s);
   if (rc != SAMKV_OK) return rc;
-  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
+  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr || !aligned16(q_rec)) return SAMKV_EINVAL;
   IntTable cu_k;
   rc = kept_table(caches, ratio, 0, 0, &cu_k);
   if (rc != SAMKV_OK) return rc;
@@ -609,7 +658,7 @@ int samkv_gather_q_v(const samkv_caches* caches, const void* const* q_cache, con
   Shape s;
   int rc = check_caches(caches, false, false, &s);
   if (rc != SAMKV_OK) return rc;
-  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr) return SAMKV_EINVAL;
+  if (q_cache == nullptr || idx == nullptr || q_rec == nullptr || !aligned16(q_rec)) return SAMKV_EINVAL;
   IntTable cu_k;
   rc = checked_cu_k(caches, s, cu_k_host, &cu_k);
   if (rc != SAMKV_OK) return rc;
@@ -640,9 +689,10 @@ int samkv_peak_read(const void* src, size_t bytes, void* sink, void* stream) {
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
                          void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   int rc = check_attn(q_rec, k_c, v_c, m_total, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
   if (rc != SAMKV_OK) return rc;
+  const AttnWs w = attn_ws(dtype, true, n_kv_heads, 0, m_total, head_dim);
+  if (w.bytes > 0 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes)) return SAMKV_EWORKSPACE;
   AttnLaunch a;
   memset(&a, 0, sizeof(a));
   a.dtype = dtype; a.d = head_dim; a.causal = 1;
@@ -650,7 +700,9 @@ int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, in
   a.q = q_rec; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
   a.n_split = 1; a.chunk = m_total;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  return dev(dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s));
+  hipError_t e = prepare_v(&a, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
+  if (e == hipSuccess) e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  return dev(e);
 }
 
 int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c, int32_t m_total,
@@ -660,8 +712,9 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
   if (rc != SAMKV_OK) return rc;
   // q_tok [Hq][Lq][d] is, per KV head, one contiguous block of G*Lq rows that all read the same K/V.
   const int rows = (n_q_heads / n_kv_heads) * n_q_tok;
-  const SplitPlan p = plan_splits(dtype, n_kv_heads, rows, m_total, head_dim);
-  if (p.n_split > 1 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < p.bytes)) return SAMKV_EWORKSPACE;
+  const AttnWs w = attn_ws(dtype, false, n_kv_heads, rows, m_total, head_dim);
+  const SplitPlan& p = w.split;
+  if (w.bytes > 0 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes)) return SAMKV_EWORKSPACE;
   AttnLaunch a;
   memset(&a, 0, sizeof(a));
   a.dtype = dtype; a.d = head_dim; a.causal = 0;
@@ -673,7 +726,8 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
     a.part_lse = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_lse);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  hipError_t e = prepare_v(&a, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
+  if (e == hipSuccess) e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
   if (e == hipSuccess && p.n_split > 1) e = launch_attn_merge(a, s);
   return dev(e);
 }
@@ -684,7 +738,7 @@ int samkv_query_attn_self(const void* q_tok, int32_t n_q_tok, const void* k_c, c
                           size_t ws_bytes, void* stream) {
   int rc = check_attn(q_tok, k_c, v_c, n_q_tok, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
   if (rc != SAMKV_OK) return rc;
-  if (k_self == nullptr || v_self == nullptr) return SAMKV_EINVAL;
+  if (k_self == nullptr || v_self == nullptr || !aligned16(k_self) || !aligned16(v_self)) return SAMKV_EINVAL;
   const SelfWs w = self_ws(n_q_heads, n_kv_heads, head_dim, n_q_tok, m_total, dtype);
   if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes) return SAMKV_EWORKSPACE;
   char* base = static_cast<char*>(ws);
@@ -696,7 +750,7 @@ int samkv_query_attn_self(const void* q_tok, int32_t n_q_tok, const void* k_c, c
                         part_lse, base + w.inner, ws_bytes - w.inner, stream);
   if (rc != SAMKV_OK) return rc;
   rc = samkv_recompute_attn(q_tok, k_self, v_self, n_q_tok, n_q_heads, n_kv_heads, head_dim, dtype, scale,
-                            part_o + n_rows * head_dim, part_lse + n_rows, nullptr, 0, stream);
+                            part_o + n_rows * head_dim, part_lse + n_rows, base + w.inner, ws_bytes - w.inner, stream);
   if (rc != SAMKV_OK) return rc;
   AttnLaunch a;
   memset(&a, 0, sizeof(a));
@@ -708,6 +762,7 @@ int samkv_query_attn_self(const void* q_tok, int32_t n_q_tok, const void* k_c, c
 int samkv_kv_update(void* k_c, void* v_c, const void* k_new, const void* v_new, int32_t m_total, int32_t n_kv_heads,
                     int32_t head_dim, int32_t dtype, int32_t mode, void* stream) {
   if (k_c == nullptr || v_c == nullptr || k_new == nullptr || v_new == nullptr) return SAMKV_EINVAL;
+  if (!aligned16(k_c) || !aligned16(v_c) || !aligned16(k_new) || !aligned16(v_new)) return SAMKV_EINVAL;
   if (m_total < 1 || n_kv_heads < 1 || (mode != SAMKV_OVERWRITE && mode != SAMKV_FUSION)) return SAMKV_EINVAL;
   if (dtype != SAMKV_F32 && dtype != SAMKV_BF16) return SAMKV_EUNSUPPORTED;
   if (head_dim != 64 && head_dim != 128) return SAMKV_EUNSUPPORTED;

@@ -124,13 +124,14 @@ def _channel_scales(w: Workload, layer: int) -> Tuple[np.ndarray, np.ndarray]:
     sk = np.exp(rng.uniform(lo, hi, size=(w.n_kv_heads, w.head_dim)))
     sv = np.exp(rng.uniform(lo, hi, size=(w.n_kv_heads, w.head_dim)))
     if w.layer_outliers:
-        # Deeper layers get stronger outlier channels in K (and in Q, which shares K's scales): that is
-        # where per-channel outliers live in real caches.  V keeps the plain [0.5, 4] scales: the bf16
-        # attention bar is an absolute 2e-2, which presumes |V| of order 10 (a bf16 value near 80 is
-        # itself only known to 0.16).
+        # Deeper layers get stronger outlier channels, in K (and in Q, which shares K's scales) and in V,
+        # each tensor with its own four seeded channels per KV head.
         for g in range(w.n_kv_heads):
             ch = rng.choice(w.head_dim, size=4, replace=False)
             sk[g, ch] *= 1.0 + layer / 8.0
+        for g in range(w.n_kv_heads):
+            ch = rng.choice(w.head_dim, size=4, replace=False)
+            sv[g, ch] *= 1.0 + layer / 8.0
     return sk, sv
 
 
@@ -236,6 +237,20 @@ def make_q_rec(w: Workload, layer: int, n_rows: int) -> np.ndarray:
     z = _rng(w, layer, _T_QREC).standard_normal((w.n_q_heads, n_rows, w.head_dim), dtype=np.float32)
     z *= np.repeat(sk, w.group, axis=0).astype(np.float32)[:, None, :]
     return round_to_dtype(z, w.dtype)
+
+
+def stack_layers(w: Workload, layers: List[LayerInputs], q_recs: List[np.ndarray]):
+    """Layers of a multi-layer workload laid out for ONE call per entry point: every document's cache holds all
+    layers as [(layer, KV head)][L][d], the Q tensors likewise [(layer, query head)][...].  Query head h of the stack
+    reads KV head h / G, which stays inside its layer, so the library needs to know nothing about layers.
+    Returns (k list, v list, q_tok, q_loc, q_rec), all float32 arrays with dtype-exact values."""
+    n_ctx = len(layers[0].k)
+    k = [np.concatenate([x.k[i] for x in layers], axis=0) for i in range(n_ctx)]
+    v = [np.concatenate([x.v[i] for x in layers], axis=0) for i in range(n_ctx)]
+    q_tok = np.concatenate([x.q_tok for x in layers], axis=0)
+    q_loc = np.concatenate([x.q_loc for x in layers], axis=1)
+    q_rec = np.concatenate(q_recs, axis=0)
+    return k, v, q_tok, q_loc, q_rec
 
 
 def make_q_cache(w: Workload, layer: int, lens: List[int]) -> List[np.ndarray]:

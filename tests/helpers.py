@@ -125,3 +125,21 @@ def upload_caches(x: synth.LayerInputs):
     k = [to_dev(a, dt) for a in x.k]
     v = [to_dev(a, dt) for a in x.v]
     return samkv.Caches(k, v, x.workload.n_q_heads)
+
+
+def check_chained(x: synth.LayerInputs, ref: OracleRun, idx_gpu: np.ndarray, k_c: np.ndarray, v_c: np.ndarray,
+                  rec_out: np.ndarray, rec_lse: np.ndarray, q_out: np.ndarray, q_lse: np.ndarray, q_rec: np.ndarray,
+                  scale: float, what: str = ""):
+    """Results of the calls chained on the GPU, every head.  The kept sets have been compared under the tie-margin
+    rule; from there on the oracle continues with the GPU's OWN kept set (identical to the oracle's wherever no score
+    sat inside the margin), so a near-tie can neither hide a head nor cascade: the compacted cache must hold
+    bit-exact copies of the rows at the kept positions, and both attentions over it must meet the attention bar.
+    Returns (max error recompute, max error query)."""
+    dt = x.workload.dtype
+    k_own, v_own = O.gather(x.k, x.v, idx_gpu, ref.cu_k)
+    assert np.array_equal(k_c, k_own) and np.array_equal(v_c, v_own), f"{what}: compacted cache"
+    o_ref, l_ref = O.attention(q_rec, k_own, v_own, scale, True)
+    e_rec = check_attention(rec_out, rec_lse, o_ref, l_ref, dt, f"{what} chained recompute")
+    o_ref, l_ref = O.attention(x.q_tok, k_own, v_own, scale, False)
+    e_q = check_attention(q_out, q_lse, o_ref, l_ref, dt, f"{what} chained query")
+    return e_rec, e_q

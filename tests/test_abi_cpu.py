@@ -172,6 +172,28 @@ def test_argument_errors_are_reported_before_any_launch(S):
     assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 5, 0.1, fake, fake, None, 0, None) == -2
     assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.0, fake, fake, None, 0, None) == -1
     assert L.samkv_query_attn(fake, 4, fake, fake, 4096, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
+    # bf16 attention needs room for the half-precision copy of V; float32 causal attention needs none
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, fake, 64, None) == -3
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, None) == -3
+    # tensors are moved with 16-byte accesses: a pointer that is not 16-byte aligned is an argument error
+    odd = ctypes.c_void_p(0x1008)
+    assert L.samkv_recompute_attn(odd, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_recompute_attn(fake, odd, fake, 8, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, odd, 8, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.1, odd, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_recompute_attn(fake, fake, fake, 8, 4, 2, 128, 1, 0.1, fake, ctypes.c_void_p(0x1002), fake, 1 << 20, None) == -1
+    assert L.samkv_query_attn(odd, 4, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(ok), odd, 4, None, 0, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_score(ctypes.byref(ok), fake, 4, odd, 2, fake, fake, 1 << 20, None) == -1
+    assert L.samkv_gather(ctypes.byref(ok), fake, 0.5, odd, fake, None) == -1
+    assert L.samkv_gather(ctypes.byref(ok), fake, 0.5, fake, odd, None) == -1
+    assert L.samkv_gather_q(ctypes.byref(ok), qp, fake, 0.5, odd, None) == -1
+    assert L.samkv_gather_q(ctypes.byref(ok), (ctypes.c_void_p * 2)(0x1000, 0x1004), fake, 0.5, fake, None) == -1
+    assert L.samkv_kv_update(fake, odd, fake, fake, 8, 2, 128, 1, 1, None) == -1
+    misaligned = _caches(S)
+    misaligned._keep[1][1] = 0x1008
+    assert L.samkv_score(ctypes.byref(misaligned), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
     assert L.samkv_query_attn(fake, 0, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
     assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, None, fake, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 30, None) == -1
     assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, fake, fake, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3

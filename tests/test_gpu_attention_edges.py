@@ -45,7 +45,8 @@ def test_recompute_attention_shapes(dtype, d, hq, hkv, m):
     scale = 1.0 / math.sqrt(d)
     out = torch.full((hq, m, d), float("nan"), device="cuda")
     lse = torch.full((hq, m), float("nan"), device="cuda")
-    S.samkv_recompute_attn(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), scale, out, lse, None)
+    ws = torch.empty((S.samkv_workspace_bytes(1, hq, hkv, d, 1, m),), dtype=torch.uint8, device="cuda")
+    S.samkv_recompute_attn(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), scale, out, lse, ws)
     rows = _rows(m, 12 if hq * m > 20000 else m, seed=m)
     heads = list(range(hq)) if hq <= 64 else sorted({0, 1, hq // 2, hq - 1} | set(range(0, hq, max(1, hq // 24))))
     G = hq // hkv
@@ -111,3 +112,33 @@ def test_query_attention_with_self_tail(dtype, d, hq, hkv, lq, m):
         o_ref[n], l_ref[n] = o[0], l[0]
     H.check_attention(out[heads].cpu().numpy(), lse[heads].cpu().numpy(), o_ref, l_ref, dtype, "query+self")
     assert torch.isfinite(out).all()
+
+
+@pytest.mark.parametrize("log2_scale", [-40, -20, 0, 7, 30, 100])
+@pytest.mark.parametrize("causal", [True, False])
+def test_bf16_attention_value_magnitudes(log2_scale, causal):
+    """The bf16 kernels multiply the weights with a half-precision copy of V that is scaled per KV head by a power of
+    two: outputs must follow V's magnitude exactly (values far outside the half-precision range included), heads
+    with very different magnitudes must not disturb each other, an all-zero head gives zeros, and a few values 2^20
+    below the head's maximum still count."""
+    import torch
+    from paper_2508_11661_amd import samkv as S
+    hq, hkv, m, d, rows = 8, 4, 300, 128, 300 if causal else 40
+    q, k, v = _data(900 + log2_scale, "bf16", hq, hkv, rows, m, d)
+    mag = np.array([2.0 ** log2_scale, 1.0, 2.0 ** -log2_scale, 0.0], np.float32)      # per KV head; exact in bf16
+    v = v * mag[:, None, None]
+    v[1, ::3] *= np.float32(2.0 ** -20)           # rows far below the head's maximum
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((hq, rows, d), float("nan"), device="cuda")
+    lse = torch.full((hq, rows), float("nan"), device="cuda")
+    ws = torch.empty((S.samkv_workspace_bytes(1, hq, hkv, d, rows, m),), dtype=torch.uint8, device="cuda")
+    args = (H.to_dev(q, "bf16"), H.to_dev(k, "bf16"), H.to_dev(v, "bf16"), scale, out, lse, ws)
+    S.samkv_recompute_attn(*args) if causal else S.samkv_query_attn(*args)
+    o_ref, l_ref = O.attention(q, k, v, scale, causal)
+    got_o, got_l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got_o)) and np.abs(got_l - l_ref).max() <= H.BF16_ABS
+    G = hq // hkv
+    for h in range(hq):
+        s = float(mag[h // G])
+        err = np.abs(got_o[h] - o_ref[h]).max()
+        assert err <= H.BF16_ABS * s, f"head {h} (values x {s:g}): error {err:.3e}"
