@@ -104,6 +104,21 @@ size_t samkv_workspace_bytes(int32_t n_ctx, int32_t n_q_heads, int32_t n_kv_head
 int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
                 int32_t w_loc, float* scores, void* ws, size_t ws_bytes, void* stream);
 
+/* samkv_score for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic and results as
+ * samkv_score; the few vectors of Eq. 1 that samkv_score keeps in the caller's workspace live in a fixed
+ * SAMKV_NOALLOC_SCRATCH_BYTES area inside the library's device image instead (every GPU the library runs on holds one
+ * copy until the process ends).  The call allocates nothing and frees nothing.
+ *   - Sizes whose vectors do not fit the area (about 4 * head_dim * n_q_heads * (n_ctx + 2) + 4 * head_dim *
+ *     n_kv_heads * n_ctx bytes) are SAMKV_EUNSUPPORTED; every other error as in samkv_score.
+ *   - All calls on one GPU share that GPU's area: two calls that overlap in time on one GPU (different streams, or
+ *     different threads) race and give undefined scores.  Calls on one stream are ordered and safe.  Nothing in the
+ *     area has to survive or be cleared between calls.
+ *   - The first call on a device looks the area's address up (hipGetSymbolAddress); make that call outside a capture. */
+#define SAMKV_NOALLOC_SCRATCH_BYTES (8u << 20)
+int samkv_score_noalloc(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc,
+                        int32_t w_loc, float* scores, void* stream);
+
 /* Sec. 3.2 selection with a fixed budget.  For document i and KV head g, keep k_i =
  * samkv_kept_count(len[i], ratio) positions: first the n_sink initial and n_local last positions
  * (they count towards k_i; n_sink + n_local > k_i for any document is SAMKV_EINVAL), then the

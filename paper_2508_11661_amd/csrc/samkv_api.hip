@@ -4,9 +4,15 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace samkv;
+
+// Scratch memory of samkv_score_noalloc: lives in the library's device image, one copy per GPU, for the life of the
+// process.  In host code this name is only a handle for hipGetSymbolAddress; kernels receive the address it returns.
+static __device__ __align__(256) unsigned char scratch[SAMKV_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -252,6 +258,37 @@ static int score_setup(const samkv_caches* caches, const void* q_tok, int32_t n_
   a->ws_base = reinterpret_cast<float*>(base + w.base);
   a->ws_qt = reinterpret_cast<float*>(base + w.qt);
   return SAMKV_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int scratch_address(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDev] = {};
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDev) return SAMKV_EDEVICE;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[d] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SAMKV_EDEVICE;
+    ptr[d] = p;
+  }
+  *out = ptr[d];
+  return SAMKV_OK;
+}
+
+int samkv_score_noalloc(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,
+                        float* scores, void* stream) {
+  Shape s;
+  const int rc = check_caches(caches, true, false, &s);
+  if (rc != SAMKV_OK) return rc;
+  if (score_ws(s.n_ctx, s.hq, s.hkv, s.d).bytes > SAMKV_NOALLOC_SCRATCH_BYTES) return SAMKV_EUNSUPPORTED;
+  void* ws = nullptr;
+  const int rs = scratch_address(&ws);
+  if (rs != SAMKV_OK) return rs;
+  // every float of the scratch area that a kernel of this call reads has been written by an earlier kernel of the
+  // same call, so nothing needs clearing between calls
+  return samkv_score(caches, q_tok, n_q_tok, q_loc, w_loc, scores, ws, SAMKV_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int samkv_score(const samkv_caches* caches, const void* q_tok, int32_t n_q_tok, const void* q_loc, int32_t w_loc,

@@ -18,7 +18,7 @@ SAMKV_MAX_CTX, SAMKV_MAX_LEN = 128, 65536
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libsamkv.so")
 
 EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_top_p", "samkv_workspace_bytes",
-           "samkv_score", "samkv_score_select", "samkv_score_select_gather", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
+           "samkv_score", "samkv_score_noalloc", "samkv_score_select", "samkv_score_select_gather", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
            "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_workspace_bytes.argtypes = [i32] * 6
     lib.samkv_score.restype = ctypes.c_int
     lib.samkv_score.argtypes = [cp, vp, i32, vp, i32, vp, vp, sz, vp]
+    lib.samkv_score_noalloc.restype = ctypes.c_int
+    lib.samkv_score_noalloc.argtypes = [cp, vp, i32, vp, i32, vp, vp]
     lib.samkv_score_select.restype = ctypes.c_int
     lib.samkv_score_select.argtypes = [cp, vp, i32, vp, i32, f32, i32, i32, vp, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     lib.samkv_score_select_gather.restype = ctypes.c_int
@@ -218,6 +220,15 @@ def samkv_score(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tenso
     assert scores.dtype == torch.float32 and tuple(scores.shape) == (caches.n_kv_heads, caches.total_len)
     _check(_lib.samkv_score(ctypes.byref(caches.c), _ptr(q_tok), n_q_tok, _ptr(q_loc), w_loc, _ptr(scores),
                             _ptr(ws), ws.numel() * ws.element_size(), _stream()), "samkv_score")
+
+
+def samkv_score_noalloc(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor], scores: torch.Tensor) -> None:
+    """samkv_score without a workspace argument: the library's own fixed scratch area serves (sizes beyond it raise)."""
+    n_q_tok = int(q_tok.shape[1])
+    w_loc = int(q_loc.shape[2]) if q_loc is not None else 0
+    assert scores.dtype == torch.float32 and tuple(scores.shape) == (caches.n_kv_heads, caches.total_len)
+    _check(_lib.samkv_score_noalloc(ctypes.byref(caches.c), _ptr(q_tok), n_q_tok, _ptr(q_loc), w_loc, _ptr(scores),
+                                    _stream()), "samkv_score_noalloc")
 
 
 def samkv_score_select(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor], ratio: float, n_sink: int,
