@@ -3,15 +3,20 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--ratio R]
 
-A step is one pass of the whole hot path (samkv_score, samkv_topk_select, samkv_gather,
-samkv_recompute_attn, samkv_query_attn) over the per-document caches of one layer (for the
-32-layer workload: over all 32 layers).  Inputs are seeded synthetic caches already resident in
-HBM; enough distinct copies are rotated that the working set exceeds twice the 256 MB Infinity
-Cache, so K is streamed from HBM and not from cache.  Prints ONE JSON line.
+A step is one pass of the whole hot path (score, selection, compaction, recompute attention, query attention) over
+the per-document caches of one layer (for the 32-layer workload: over all 32 layers).  Inputs are the seeded
+synthetic caches of `paper_2508_11661_amd/synth.py`, already resident in HBM; enough distinct copies are rotated
+that the working set exceeds twice the 256 MB Infinity Cache, so K is streamed from HBM and not from cache.
+Prints ONE JSON line.
+
+Default workload: `large_cache_stress` (64 documents x 4096 tokens, 64/8 heads, d = 128, 256 query tokens, 15 %),
+the largest single-GPU configuration.  Beside the headline the line carries
+  secondary   the same step on the small `llama3_8b_layer` workload (launch- and latency-bound; context only)
+  sweep       the five separate calls on `mistral_7b_sweep` at 5, 10, 15 and 25 % budget (the crossover table)
+  measured_peaks, cpu_baseline
 
 The timed region launches the calls eagerly and brackets only the dominant call with HIP events (its average
-duration feeds the roofline figure); the per-call table comes from a second, untimed pass with every call
-bracketed, and `hip_graph` repeats the timed steps as replays of captured HIP graphs.
+duration feeds the roofline figure); the per-call table comes from a second, untimed pass with every call bracketed.
 """
 from __future__ import annotations
 
@@ -19,7 +24,6 @@ import argparse
 import json
 import math
 import os
-import re
 import sys
 import time
 
@@ -30,6 +34,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 FP32_VALU_PEAK_TFLOPS = 157.3
+RIDGE = MFMA_BF16_PEAK_TFLOPS / HBM_PEAK_GBS * 1e3   # flop per byte above which a bf16 kernel is MFMA-bound
 KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")          # the five entry points of the path
 STEP = ("score_select_gather", "recompute_attn", "query_attn")                   # what a step launches: the first three fused
 EXTRA = ("score_select",)                                                        # also timed per call, outside the step
@@ -56,6 +61,31 @@ def algorithmic_work(w, lens, m, n_q_tok):
         "query_attn": {"bytes": 2 * m * hkv * d * e + hq * n_q_tok * (d * e + (d + 1) * 4),
                        "flops": 4 * hq * d * n_q_tok * m},
     }
+
+
+def bound_of(name, w, work):
+    """Which roofline bounds a call: HBM for score / select / gather; the matrix cores for the causal attention; for
+    the query attention whichever its arithmetic intensity puts lower (HBM below the ridge of about 310 flop/B)."""
+    if not name.endswith("attn"):
+        return "hbm"
+    if w.dtype != "bf16":
+        return "alu"
+    if name == "query_attn" and work[name]["flops"] / work[name]["bytes"] < RIDGE:
+        return "hbm"
+    return "mfma"
+
+
+def kernel_row(name, w, work, ms, layers_per_call=1):
+    gbs = work[name]["bytes"] * layers_per_call / (ms * 1e-3) / 1e9
+    tfl = work[name]["flops"] * layers_per_call / (ms * 1e-3) / 1e12
+    bound = bound_of(name, w, work)
+    row = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2), "bound": bound,
+           "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
+    if name.endswith("attn"):
+        peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+        row["frac_compute"] = round(tfl / peak, 4)
+    row["frac"] = row["frac_hbm"] if bound == "hbm" else row["frac_compute"]
+    return row
 
 
 def read_traffic(workload, kernel: str):
@@ -130,8 +160,16 @@ def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
     sample = (f"whole layer, every step of the path, mean of {len(totals)} passes" if rows is None else
               f"score/select/gather/query attention in full; recompute attention on {len(rows)} of {m} rows per "
               f"head ({frac:.3%} of the causal pairs), time extrapolated by pair count")
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
     return {"value": sum(layer.lens) / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": sample, "seconds_measured": round(wall, 2), "ms_per_step_extrapolated": round(total * 1e3, 1)}
+            "sample": sample, "seconds_measured": round(wall, 2), "ms_per_step_extrapolated": round(total * 1e3, 1),
+            "host": {"nproc": os.cpu_count(), "cpus_usable_by_this_process": usable,
+                     "OMP_NUM_THREADS": os.environ.get("OMP_NUM_THREADS"),
+                     "note": "`cores` = process CPU time / wall time of the oracle run: numpy's own loops run on one "
+                             "thread, its matrix products on as many as the BLAS it links takes"}}
 
 
 def measured_peaks(samkv, iters=7):
@@ -176,141 +214,242 @@ def measured_peaks(samkv, iters=7):
     return out
 
 
-def at_scale(samkv, iters=5):
-    """Kernel timings at the shapes of the largest workload (64 documents x 4096 tokens, 64/8 heads, d = 128,
-    256 query tokens, 15 % budget), where the kernels are bandwidth- or MFMA-bound instead of latency-bound.
-    Shapes only: device-generated Gaussian bf16 tensors, HIP-event timing, the same entry points.  This is
-    context for the roofline fractions; the headline value above stays the timed workload's."""
+class Workbench:
+    """Device inputs and buffers of one workload at one budget, and the calls of the path on them."""
+
+    def __init__(self, samkv, synth, w, ratio, n_layers, layout, n_streams_arg, caches_from=None):
+        """`caches_from`: another Workbench of the same single-layer workload whose uploaded caches and query tensors
+        are reused (they do not depend on the budget); only the kept tokens' query states and the buffers are new."""
+        import torch
+        self.samkv, self.w, self.ratio, self.n_layers = samkv, w, ratio, n_layers
+        to_dev = samkv.upload
+        e = 2 if w.dtype == "bf16" else 4
+        self.scale = scale = 1.0 / math.sqrt(w.head_dim)
+        self.m = m = sum(samkv.samkv_kept_count(n, ratio) for n in w.lens)
+        if caches_from is not None:
+            o = caches_from
+            self.layers_np, self.n_rot, self.stacked, self.layers_per_call = o.layers_np, o.n_rot, False, 1
+            q_rec = to_dev(synth.make_q_rec(w, 0, m), w.dtype)
+            self.sets = [dict(s, q_rec=q_rec) for s in o.sets]
+        else:
+            self._upload(synth, w, n_layers, layout, m, e)
+        self._finish(samkv, w, ratio, scale, n_streams_arg)
+
+    def _upload(self, synth, w, n_layers, layout, m, e):
+        samkv = self.samkv
+        to_dev = samkv.upload
+        # ---- inputs: n_layers layers, replicated until the K/V working set passes 512 MB
+        self.layers_np = [synth.make_layer(w, l) for l in range(n_layers)]
+        kv_bytes = 2 * sum(w.lens) * w.n_kv_heads * w.head_dim * e * n_layers
+        self.n_rot = max(1, min(16, math.ceil(512e6 / kv_bytes)))
+        # Layout of a multi-layer workload.  "stacked": every document's cache holds all layers, [(layer, KV head)][L][d],
+        # and so do the Q tensors (synth.stack_layers); ONE call per entry point serves all layers: 4 launches of
+        # full-chip size per step instead of 4 small ones per layer.  "per-layer": one set of calls per layer.
+        self.stacked = n_layers > 1 and layout == "stacked"
+        self.layers_per_call = n_layers if self.stacked else 1
+        self.sets = []
+        for rot in range(self.n_rot):
+            if self.stacked:
+                k, v, q_tok, q_loc, q_rec = synth.stack_layers(w, self.layers_np,
+                                                               [synth.make_q_rec(w, l, m) for l in range(n_layers)])
+                self.sets.append(dict(caches=samkv.Caches([to_dev(a, w.dtype) for a in k], [to_dev(a, w.dtype) for a in v],
+                                                          w.n_q_heads * n_layers),
+                                      q_tok=to_dev(q_tok, w.dtype), q_loc=to_dev(q_loc, w.dtype), q_rec=to_dev(q_rec, w.dtype)))
+                del k, v
+                continue
+            for l, x in enumerate(self.layers_np):
+                k = [to_dev(a, w.dtype) for a in x.k]
+                v = [to_dev(a, w.dtype) for a in x.v]
+                self.sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads), q_tok=to_dev(x.q_tok, w.dtype),
+                                      q_loc=to_dev(x.q_loc, w.dtype),
+                                      q_rec=to_dev(synth.make_q_rec(w, l, m), w.dtype)))
+
+    def _finish(self, samkv, w, ratio, scale, n_streams_arg):
+        import torch
+        n_layers, m = self.n_layers, self.m
+        self.calls_per_step = 1 if self.stacked else n_layers
+        # The layers of a multi-layer workload are independent (per-layer caches, stored Q states as inputs), so they
+        # may be spread over `n_streams` HIP streams of default priority, each with its own buffers.
+        self.n_streams = n_streams_arg or (1 if self.calls_per_step == 1 else 2)
+        self.bufs = [samkv.alloc_layer_buffers(self.sets[0]["caches"], w.n_q_tok, ratio) for _ in range(self.n_streams)]
+        self.streams = ([torch.cuda.current_stream()] if self.n_streams == 1
+                        else [torch.cuda.Stream() for _ in range(self.n_streams)])
+        torch.cuda.synchronize()
+        S = samkv
+        self.calls = {
+            "score": lambda s, b: S.samkv_score(s["caches"], s["q_tok"], s["q_loc"], b.scores, b.ws),
+            "select": lambda s, b: S.samkv_topk_select(b.scores, s["caches"], ratio, 0, 0, b.idx, b.cu_k_dev, b.ws),
+            "gather": lambda s, b: S.samkv_gather(s["caches"], b.idx, ratio, b.k_c, b.v_c),
+            "recompute_attn": lambda s, b: S.samkv_recompute_attn(s["q_rec"], b.k_c, b.v_c, scale, b.rec_out, b.rec_lse, b.ws),
+            "query_attn": lambda s, b: S.samkv_query_attn(s["q_tok"], b.k_c, b.v_c, scale, b.q_out, b.q_lse, b.ws),
+            "score_select": lambda s, b: S.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, b.idx,
+                                                              b.cu_k_dev, b.ws),
+            "score_select_gather": lambda s, b: S.samkv_score_select_gather(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0,
+                                                                            None, b.idx, b.cu_k_dev, b.k_c, b.v_c, b.ws),
+        }
+        self.work = algorithmic_work(w, w.lens, m, w.n_q_tok)
+
+    def step(self, i, events=None, only=None, names=STEP):
+        """One pass of the hot path.  `events`: dict name -> list of (start, end) HIP events on the launch stream,
+        recorded around every call, or only around the call named `only`."""
+        import torch
+        for l in range(self.calls_per_step):
+            s = self.sets[(i * self.calls_per_step + l) % len(self.sets)]
+            lane = (i * self.calls_per_step + l) % self.n_streams   # consecutive passes alternate streams
+            b = self.bufs[lane]
+            with torch.cuda.stream(self.streams[lane]):
+                for name in names:
+                    if events is not None and (only is None or only == name):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        self.calls[name](s, b)
+                        e1.record()
+                        events[name].append((e0, e1))
+                    else:
+                        self.calls[name](s, b)
+
+    def run(self, steps, warmup, per_call_steps=50):
+        """Probe for the dominant call, warm up, time `steps` steps (events around the dominant call only), then an
+        untimed pass with every call bracketed.  Returns (ms_per_step, dominant call, per_kernel table)."""
+        import numpy as np
+        import torch
+        mean_ms = lambda evs: float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        probe = {name: [] for name in STEP}
+        n_probe = 12 if self.calls_per_step * self.n_layers <= 4 and self.m < 8192 else 3
+        for name in STEP:                                           # one call bracketed at a time, as in the timed region
+            for i in range(n_probe):
+                self.step(i, probe, only=name)
+        torch.cuda.synchronize()
+        dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 2:]))
+
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        dom_events = {dom: []}
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(warmup + i, dom_events, only=dom)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+
+        events = {name: [] for name in STEP + KERNELS + EXTRA}
+        for i in range(min(steps, per_call_steps)):
+            self.step(warmup + steps + i, events)
+            self.step(warmup + steps + i, events, names=KERNELS)
+            self.step(warmup + steps + i, events, names=EXTRA)
+        torch.cuda.synchronize()
+        events[dom] = dom_events[dom]          # the dominant call's figure is the one from the timed region
+        w, work = self.w, self.work
+        per_kernel = {}
+        for name in STEP + tuple(n for n in KERNELS + EXTRA if n not in STEP):
+            # the dominant call: mean over the timed region; the others: median of the untimed pass
+            samples = [a.elapsed_time(b) for a, b in events[name]]
+            ms = float(np.mean(samples) if name == dom else np.median(samples))
+            per_kernel[name] = kernel_row(name, w, work, ms, self.layers_per_call)
+        ss_ms = per_kernel["score"]["ms"] + per_kernel["select"]["ms"]
+        ss_gbs = (work["score"]["bytes"] + self.m * w.n_kv_heads * 4) * self.layers_per_call / (ss_ms * 1e-3) / 1e9
+        per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
+                                      "note": "the two separate calls as one K-streaming stage, for comparison with the "
+                                              "fused calls (score_select, and score_select_gather that the timed step launches)"}
+        return ms_per_step, dom, per_kernel
+
+    def graph_ms(self, steps, warmup):
+        """The same steps as replays of captured HIP graphs (one per rotated input set)."""
+        import torch
+        if len(self.sets) > 64 or self.n_streams != 1:
+            return None
+        side = torch.cuda.Stream()
+        graphs = []
+        saved = self.streams[0]
+        self.streams[0] = side                  # step() launches on streams[0]: capture on the side stream
+        with torch.cuda.stream(side):
+            for gi in range(len(self.sets) // self.calls_per_step):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    self.step(gi)
+                graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(steps):
+            graphs[(warmup + i) % len(graphs)].replay()
+        torch.cuda.synchronize()
+        self.streams[0] = saved
+        return (time.perf_counter() - t1) / steps * 1e3
+
+    def two_stream_ms(self, steps, warmup):
+        """Independent requests side by side: the same steps alternating between two streams with their own buffers."""
+        import torch
+        if self.n_streams != 1 or self.calls_per_step != 1:
+            return None
+        saved = (self.n_streams, self.bufs, self.streams)
+        self.n_streams = 2
+        self.bufs = [saved[1][0], self.samkv.alloc_layer_buffers(self.sets[0]["caches"], self.w.n_q_tok, self.ratio)]
+        self.streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(steps):
+            self.step(warmup + i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t1) / steps * 1e3
+        self.n_streams, self.bufs, self.streams = saved
+        return ms
+
+
+def sweep(samkv, synth, iters=30, warmup=8):
+    """The five separate calls of the path on `mistral_7b_sweep` at each of its budgets: score is flat in the budget,
+    gather and the query attention grow with r, the recompute attention with r^2.  Per call: median of `iters`
+    event-bracketed launches after `warmup`, inputs rotated past the Infinity Cache."""
+    import numpy as np
     import torch
-    w = __import__("paper_2508_11661_amd.synth", fromlist=["WORKLOADS"]).WORKLOADS["large_cache_stress"]
-    g = torch.Generator(device="cuda").manual_seed(1234)
-    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=g).to(torch.bfloat16)
-    k = [rnd(w.n_kv_heads, w.ctx_len, w.head_dim) for _ in range(w.n_ctx)]
-    v = [rnd(w.n_kv_heads, w.ctx_len, w.head_dim) for _ in range(w.n_ctx)]
-    caches = samkv.Caches(k, v, w.n_q_heads)
-    q_tok = rnd(w.n_q_heads, w.n_q_tok, w.head_dim)
-    q_loc = rnd(w.n_ctx, w.n_q_heads, w.w_loc, w.head_dim)
-    m = w.n_ctx * samkv.samkv_kept_count(w.ctx_len, 0.15)
-    q_rec = rnd(w.n_q_heads, m, w.head_dim)
-    buf = samkv.alloc_layer_buffers(caches, w.n_q_tok, 0.15)
-    scale = 1.0 / math.sqrt(w.head_dim)
-    calls = {
-        "score": lambda: samkv.samkv_score(caches, q_tok, q_loc, buf.scores, buf.ws),
-        "select": lambda: samkv.samkv_topk_select(buf.scores, caches, 0.15, 0, 0, buf.idx, buf.cu_k_dev, buf.ws),
-        "gather": lambda: samkv.samkv_gather(caches, buf.idx, 0.15, buf.k_c, buf.v_c),
-        "recompute_attn": lambda: samkv.samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws),
-        "query_attn": lambda: samkv.samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws),
-    }
-    work = algorithmic_work(w, w.lens, m, w.n_q_tok)
-    res = {"workload": w.name, "data": "device-generated Gaussian bf16, shapes only", "iters": iters}
-    for name in KERNELS:                      # in path order, so select/gather/attention see real scores and indices
-        calls[name]()
-    torch.cuda.synchronize()
-    for name in KERNELS:
-        ev = []
-        for _ in range(iters):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            calls[name]()
-            b.record()
-            ev.append((a, b))
+    w = synth.WORKLOADS["mistral_7b_sweep"]
+    names = KERNELS + ("score_select_gather",)
+    rows, first = [], None
+    for ratio in w.ratios:
+        wb = Workbench(samkv, synth, w, ratio, 1, "per-layer", 1, caches_from=first)
+        first = first or wb
+        for i in range(warmup):
+            wb.step(i, names=names)
+        events = {n: [] for n in names}
+        for i in range(iters):
+            wb.step(warmup + i, events, names=names)
         torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
-        res[name] = {"ms": round(ms, 4), "GB/s": round(work[name]["bytes"] / ms / 1e6, 1),
-                     "TFLOP/s": round(work[name]["flops"] / ms / 1e9, 1),
-                     "frac_hbm": round(work[name]["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
-                     "frac_mfma": round(work[name]["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
-    ss_ms = res["score"]["ms"] + res["select"]["ms"]
-    ss_bytes = work["score"]["bytes"] + m * w.n_kv_heads * 4
-    ss_gbs = ss_bytes / ss_ms / 1e6
-    res["score+select"] = {"ms": round(ss_ms, 4), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4)}
-    fused = lambda: samkv.samkv_score_select(caches, q_tok, q_loc, 0.15, 0, 0, None, buf.idx, buf.cu_k_dev, buf.ws)
-    fused()
-    torch.cuda.synchronize()
-    ev = []
-    for _ in range(iters):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        fused()
-        b.record()
-        ev.append((a, b))
-    torch.cuda.synchronize()
-    ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
-    res["score_select_fused"] = {"ms": round(ms, 4), "GB/s": round(ss_bytes / ms / 1e6, 1),
-                                 "frac_hbm": round(ss_bytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
-
-    # the causal attention once more on all-zero operands: same instruction stream, far fewer bits toggling.  The
-    # difference to the figure above is what the device's power limit costs on real data.
-    zq, zk, zv = torch.zeros_like(q_rec), torch.zeros_like(buf.k_c), torch.zeros_like(buf.v_c)
-    zcall = lambda: samkv.samkv_recompute_attn(zq, zk, zv, scale, buf.rec_out, buf.rec_lse, buf.ws)
-    zcall()
-    torch.cuda.synchronize()
-    ev = []
-    for _ in range(iters):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        zcall()
-        b.record()
-        ev.append((a, b))
-    torch.cuda.synchronize()
-    ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
-    res["recompute_attn_zero_operands"] = {"ms": round(ms, 4),
-                                           "TFLOP/s": round(work["recompute_attn"]["flops"] / ms / 1e9, 1),
-                                           "note": "same launch on all-zero Q, K, V: not power-limited"}
-    del zq, zk, zv
-
-    # block-level variant of the selection (64-token blocks, 1 initial + 2 local blocks forced, per-document share
-    # 0.15 of the middle blocks), with and without the cross-document filter, and the gather that follows each
-    block, p = 64, [0.15] * w.n_ctx
-    nb = sum(-(-n // block) for n in w.lens)
-    bs = torch.empty((w.n_kv_heads, nb), dtype=torch.float32, device="cuda")
-    bws = torch.empty(samkv.samkv_block_workspace_bytes(caches, block), dtype=torch.uint8, device="cuda")
-    samkv.samkv_block_scores(buf.scores, caches, block, bs)
-    mb = samkv.samkv_block_select_count(caches, block, p, 1, 2)
-    idx_b = torch.empty((w.n_kv_heads, mb), dtype=torch.int32, device="cuda")
-    cu = samkv.samkv_block_select(bs, caches, block, p, 1, 2, idx_b, None, bws)
-    mf = samkv.samkv_block_filter_count(caches, block, p, 1, 2)
-    gidx = torch.empty((w.n_kv_heads, mf), dtype=torch.int32, device="cuda")
-    kb, vb = (torch.empty((w.n_kv_heads, mb, w.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(2))
-    kf, vf = (torch.empty((w.n_kv_heads, mf, w.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(2))
-    row = w.head_dim * 2
-    bcalls = {
-        "block_scores": (lambda: samkv.samkv_block_scores(buf.scores, caches, block, bs), 4 * w.n_kv_heads * (sum(w.lens) + nb)),
-        "block_select": (lambda: samkv.samkv_block_select(bs, caches, block, p, 1, 2, idx_b, None, bws), 4 * w.n_kv_heads * (nb + mb)),
-        "gather_v": (lambda: samkv.samkv_gather_v(caches, idx_b, cu, kb, vb), w.n_kv_heads * mb * (4 * row + 4)),
-        "block_select_filter": (lambda: samkv.samkv_block_select_filter(bs, caches, block, p, 1, 2, gidx, bws), 4 * w.n_kv_heads * (nb + mf)),
-        "gather_g": (lambda: samkv.samkv_gather_g(caches, gidx, kf, vf), w.n_kv_heads * mf * (4 * row + 4)),
-    }
-    blk = {"block": block, "kept_tokens": mb, "kept_tokens_after_filter": mf}
-    for name, (fn, nbytes) in bcalls.items():
-        fn()
-        torch.cuda.synchronize()
-        ev = []
-        for _ in range(iters):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            fn()
-            b.record()
-            ev.append((a, b))
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in ev)[iters // 2]
-        blk[name] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
-    res["block_level"] = blk
-    return res
+        row = {"ratio": ratio, "kept_per_ctx": wb.m // w.n_ctx, "m_total": wb.m}
+        for n in names:
+            ms = float(np.median([a.elapsed_time(b) for a, b in events[n]]))
+            row[n] = kernel_row(n, w, wb.work, ms)
+        row["five_calls_ms"] = round(sum(row[n]["ms"] for n in KERNELS), 5)
+        row["step_ms"] = round(sum(row[n]["ms"] for n in STEP), 5)
+        hbm = {n: row[n]["ms"] for n in ("score", "select", "gather")}
+        row["largest_hbm_bound_call"] = max(hbm, key=hbm.get)
+        row["gather_bytes_over_score_bytes"] = round(wb.work["gather"]["bytes"] / wb.work["score"]["bytes"], 3)
+        row["recompute_over_score_time"] = round(row["recompute_attn"]["ms"] / row["score"]["ms"], 2)
+        rows.append(row)
+        if wb is not first:
+            del wb
+        torch.cuda.empty_cache()
+    return {"workload": w.name, "iters": iters, "warmup": warmup, "input_copies_rotated": first.n_rot, "rows": rows,
+            "note": "score streams all of K whatever the budget; gather bytes reach score bytes at r = 0.25 "
+                    "(4 d e r against d e per token-head); the recompute attention grows with r^2"}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama3_8b_layer")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="large_cache_stress")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None, help="layers of a multi-layer workload to run (default all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
-    ap.add_argument("--no-at-scale", action="store_true",
-                    help="skip the extra kernel timings at the shapes of the large-cache workload")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the extra timing of the small llama3_8b_layer workload")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the budget sweep on mistral_7b_sweep")
     ap.add_argument("--layout", choices=("stacked", "per-layer"), default="stacked",
                     help="multi-layer workloads: all layers in one tensor per document and one call per entry point, "
                          "or one set of calls per layer")
@@ -330,10 +469,8 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     from paper_2508_11661_amd import samkv, synth
-    to_dev = samkv.upload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -341,149 +478,13 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     ratio = args.ratio if args.ratio is not None else (0.15 if 0.15 in w.ratios else w.ratios[0])
     n_layers = args.layers or w.n_layers
-    e = 2 if w.dtype == "bf16" else 4
-    scale = 1.0 / math.sqrt(w.head_dim)
 
-    # ---- inputs: n_layers layers, replicated until the K/V working set passes 512 MB
-    layers_np = [synth.make_layer(w, l) for l in range(n_layers)]
-    m = sum(samkv.samkv_kept_count(n, ratio) for n in w.lens)
-    kv_bytes = 2 * sum(w.lens) * w.n_kv_heads * w.head_dim * e * n_layers
-    n_rot = max(1, min(16, math.ceil(512e6 / kv_bytes)))
-    # Layout of a multi-layer workload.  "stacked": every document's cache holds all layers, [(layer, KV head)][L][d],
-    # and so do the Q tensors; the library knows nothing about layers (a head is a head, query head h reads KV head
-    # h / G, which stays inside its layer), so ONE call per entry point serves all layers: 4 launches of full-chip
-    # size per step instead of 4 small ones per layer.  "per-layer": one set of calls per layer.
-    stacked = n_layers > 1 and args.layout == "stacked"
-    layers_per_call = n_layers if stacked else 1
-    sets = []
-    for rot in range(n_rot):
-        if stacked:
-            cat = lambda arrs, axis=0: to_dev(np.concatenate(arrs, axis=axis), w.dtype)
-            k = [cat([x.k[i] for x in layers_np]) for i in range(w.n_ctx)]
-            v = [cat([x.v[i] for x in layers_np]) for i in range(w.n_ctx)]
-            sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads * n_layers), q_tok=cat([x.q_tok for x in layers_np]),
-                             q_loc=cat([x.q_loc for x in layers_np], axis=1),
-                             q_rec=cat([synth.make_q_rec(w, l, m) for l in range(n_layers)])))
-            continue
-        for l, x in enumerate(layers_np):
-            k = [to_dev(a, w.dtype) for a in x.k]
-            v = [to_dev(a, w.dtype) for a in x.v]
-            sets.append(dict(caches=samkv.Caches(k, v, w.n_q_heads), q_tok=to_dev(x.q_tok, w.dtype),
-                             q_loc=to_dev(x.q_loc, w.dtype),
-                             q_rec=to_dev(synth.make_q_rec(w, l, m), w.dtype)))
-    calls_per_step = 1 if stacked else n_layers
-    # The layers of a multi-layer workload are independent (per-layer caches, stored Q states as inputs), so they are
-    # spread over `n_streams` HIP streams of default priority, each with its own buffers: the tail of one layer's
-    # causal attention (a few long row tiles) overlaps with the next layer's first kernels.
-    n_streams = args.streams or (1 if calls_per_step == 1 else 2)
-    bufs = [samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio) for _ in range(n_streams)]
-    streams = [torch.cuda.current_stream()] if n_streams == 1 else [torch.cuda.Stream() for _ in range(n_streams)]
-    torch.cuda.synchronize()
-
-    calls = {
-        "score": lambda s, b: samkv.samkv_score(s["caches"], s["q_tok"], s["q_loc"], b.scores, b.ws),
-        "select": lambda s, b: samkv.samkv_topk_select(b.scores, s["caches"], ratio, 0, 0, b.idx, b.cu_k_dev, b.ws),
-        "gather": lambda s, b: samkv.samkv_gather(s["caches"], b.idx, ratio, b.k_c, b.v_c),
-        "recompute_attn": lambda s, b: samkv.samkv_recompute_attn(s["q_rec"], b.k_c, b.v_c, scale, b.rec_out, b.rec_lse, b.ws),
-        "query_attn": lambda s, b: samkv.samkv_query_attn(s["q_tok"], b.k_c, b.v_c, scale, b.q_out, b.q_lse, b.ws),
-        "score_select": lambda s, b: samkv.samkv_score_select(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0, None, b.idx,
-                                                              b.cu_k_dev, b.ws),
-        "score_select_gather": lambda s, b: samkv.samkv_score_select_gather(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0,
-                                                                            None, b.idx, b.cu_k_dev, b.k_c, b.v_c, b.ws),
-    }
-
-    def step(i, events=None, only=None, names=STEP):
-        """One pass of the hot path.  `events`: dict name -> list of (start, end) HIP events on the launch stream,
-        recorded around every call, or only around the call named `only`."""
-        for l in range(calls_per_step):
-            s = sets[(i * calls_per_step + l) % len(sets)]
-            lane = (i * calls_per_step + l) % n_streams   # consecutive passes (layers, or whole steps) alternate streams
-            b = bufs[lane]
-            with torch.cuda.stream(streams[lane]):
-                for name in names:
-                    if events is not None and (only is None or only == name):
-                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                        e0.record()
-                        calls[name](s, b)
-                        e1.record()
-                        events[name].append((e0, e1))
-                    else:
-                        calls[name](s, b)
-
-    def mean_ms(evs):
-        return float(np.mean([a.elapsed_time(b) for a, b in evs]))
-
-    # untimed: which call dominates (events around every call cost a few microseconds each, so the timed region
-    # below carries them only around that one call)
-    probe = {name: [] for name in STEP}
-    n_probe = 12 if calls_per_step * n_layers <= 4 else 3       # short steps: the first few are not representative
-    for name in STEP:                                           # one call bracketed at a time, as in the timed region
-        for i in range(n_probe):
-            step(i, probe, only=name)
-    torch.cuda.synchronize()
-    dom = max(STEP, key=lambda n: mean_ms(probe[n][len(probe[n]) // 2:]))
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    dom_events = {dom: []}
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, dom_events, only=dom)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
-    # untimed again: every call bracketed, for the per-call table (the step's fused call, then the five entry points)
-    events = {name: [] for name in STEP + KERNELS + EXTRA}
-    for i in range(min(args.steps, 50)):
-        step(args.warmup + args.steps + i, events)
-        step(args.warmup + args.steps + i, events, names=KERNELS)
-        step(args.warmup + args.steps + i, events, names=EXTRA)
-    torch.cuda.synchronize()
-    events[dom] = dom_events[dom]          # the dominant call's figure is the one from the timed region
-
-    # the same K steps as replays of captured HIP graphs (one graph per rotated input set): what a serving loop
-    # would launch.  Reported beside the eager figure, not instead of it.
-    graph_ms = None
-    if args.graph and len(sets) <= 64 and n_streams == 1:
-        side = torch.cuda.Stream()
-        graphs = []
-        streams[0] = side                  # step() launches on streams[0]: capture on the side stream
-        with torch.cuda.stream(side):
-            for gi in range(len(sets) // calls_per_step):
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=side):
-                    step(gi)
-                graphs.append(g)
-        torch.cuda.synchronize()
-        for i in range(args.warmup):
-            graphs[i % len(graphs)].replay()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for i in range(args.steps):
-            graphs[(args.warmup + i) % len(graphs)].replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t1) / args.steps * 1e3
-
-    # independent requests side by side: the same K steps alternating between two streams with their own buffers.
-    # A throughput figure for a serving loop (a step here is no longer a latency); reported beside the main one.
-    two_ms = None
-    if n_streams == 1 and calls_per_step == 1 and not args.no_two_streams and ms_per_step < 5.0:
-        saved = (n_streams, bufs, streams)
-        n_streams = 2
-        bufs = [saved[1][0], samkv.alloc_layer_buffers(sets[0]["caches"], w.n_q_tok, ratio)]
-        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-        torch.cuda.synchronize()
-        for i in range(args.warmup):
-            step(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for i in range(args.steps):
-            step(args.warmup + i)
-        torch.cuda.synchronize()
-        two_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        n_streams, bufs, streams = saved
+    wb = Workbench(samkv, synth, w, ratio, n_layers, args.layout, args.streams)
+    ms_per_step, dom, per_kernel = wb.run(args.steps, args.warmup)
+    m, work = wb.m, wb.work
+    short = ms_per_step < 5.0
+    graph_ms = wb.graph_ms(args.steps, args.warmup) if args.graph and short else None
+    two_ms = wb.two_stream_ms(args.steps, args.warmup) if not args.no_two_streams and short else None
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -492,43 +493,25 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    work = algorithmic_work(w, w.lens, m, w.n_q_tok)
-    per_kernel = {}
-    for name in STEP + tuple(n for n in KERNELS + EXTRA if n not in STEP):
-        # the dominant call: mean over the timed region; the others: median of the untimed pass, whose first call of a
-        # kernel pays for loading it and which an occasional host hiccup of tens of milliseconds would distort
-        samples = [a.elapsed_time(b) for a, b in events[name]]
-        ms = float(np.mean(samples) if name == dom else np.median(samples))
-        gbs = work[name]["bytes"] * layers_per_call / (ms * 1e-3) / 1e9
-        tfl = work[name]["flops"] * layers_per_call / (ms * 1e-3) / 1e12
-        per_kernel[name] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
-                            "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)}
-        if name.endswith("attn"):
-            peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
-            per_kernel[name]["frac_compute"] = round(tfl / peak, 4)
-
-    ss_ms = per_kernel["score"]["ms"] + per_kernel["select"]["ms"]
-    ss_gbs = (work["score"]["bytes"] + m * w.n_kv_heads * 4) * layers_per_call / (ss_ms * 1e-3) / 1e9
-    per_kernel["score+select"] = {"ms": round(ss_ms, 5), "GB/s": round(ss_gbs, 1), "frac_hbm": round(ss_gbs / HBM_PEAK_GBS, 4),
-                                  "note": "the two separate calls as one K-streaming stage, for comparison with the "
-                                          "fused calls (score_select, and score_select_gather that the timed step launches)"}
-    if dom.endswith("attn") and w.dtype == "bf16":
-        roof = {"kernel": dom, "bound": "mfma", "achieved": per_kernel[dom]["TFLOP/s"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS, 4)}
-    elif dom.endswith("attn"):
-        roof = {"kernel": dom, "bound": "alu", "achieved": per_kernel[dom]["TFLOP/s"], "peak": FP32_VALU_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(per_kernel[dom]["TFLOP/s"] / FP32_VALU_PEAK_TFLOPS, 4)}
+    bound = per_kernel[dom]["bound"]
+    if bound == "hbm":
+        roof = {"kernel": dom, "bound": "hbm", "achieved": per_kernel[dom]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        roof = {"kernel": dom, "bound": "hbm", "achieved": per_kernel[dom]["GB/s"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(per_kernel[dom]["GB/s"] / HBM_PEAK_GBS, 4)}
+        roof = {"kernel": dom, "bound": bound, "achieved": per_kernel[dom]["TFLOP/s"],
+                "peak": MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["avg_launch_ms"] = per_kernel[dom]["ms"]
     roof["traffic"] = read_traffic(w, dom)
-    roof["algorithmic"] = (work[dom]["flops"] if roof["bound"] != "hbm" else work[dom]["bytes"]) * layers_per_call
+    roof["algorithmic"] = (work[dom]["flops"] if bound != "hbm" else work[dom]["bytes"]) * wb.layers_per_call
+    if dom.endswith("attn") and w.dtype == "bf16":
+        roof["note"] = ("the call = two small launches that rewrite V as scaled half precision (not counted as "
+                        "algorithmic work) + the attention kernel; achieved = algorithmic flop / duration of the call")
 
+    tokens = sum(w.lens) * n_layers
     out = {
         "metric": "KV tokens scored per second through the whole sparse-prefill hot path "
                   "(score+select+gather+recompute_attn+query_attn)",
-        "value": round(sum(w.lens) * n_layers / (ms_per_step * 1e-3), 1),
+        "value": round(tokens / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
@@ -538,8 +521,11 @@ def main() -> int:
         "config": {"workload": w.name, "n_layers": n_layers, "n_ctx": w.n_ctx, "ctx_len": w.ctx_len,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_q_tok": w.n_q_tok, "budget_ratio": ratio, "kept_per_ctx": m // w.n_ctx, "m_total": m,
-                   "input_copies_rotated": n_rot, "streams": n_streams,
-                   "layout": "stacked: one call per entry point serves all layers" if stacked else "per-layer calls"},
+                   "input_copies_rotated": wb.n_rot, "streams": wb.n_streams,
+                   "layout": "stacked: one call per entry point serves all layers" if wb.stacked else "per-layer calls",
+                   "step": "samkv_score_select_gather (scores = NULL: the scores stay on chip, only the kept positions "
+                           "and the compacted rows are written), samkv_recompute_attn, samkv_query_attn",
+                   "inputs": "seeded synthetic caches (synth.make_layer), resident in HBM"},
         "per_kernel": per_kernel,
         "roofline": roof,
     }
@@ -552,17 +538,33 @@ def main() -> int:
         elif roof["bound"] == "hbm":
             roof["frac_of_measured_peak"] = round(roof["achieved"] / mp["read_gbs"], 4)
     if two_ms is not None:
-        out["two_streams"] = {"ms_per_step": round(two_ms, 4), "value": round(sum(w.lens) * n_layers / (two_ms * 1e-3), 1),
+        out["two_streams"] = {"ms_per_step": round(two_ms, 4), "value": round(tokens / (two_ms * 1e-3), 1),
                               "unit": "tokens/s", "note": "the same steps as independent requests alternating between two "
                                                           "HIP streams: throughput, not the latency of a step"}
     if graph_ms is not None:
-        out["hip_graph"] = {"ms_per_step": round(graph_ms, 4), "value": round(sum(w.lens) * n_layers / (graph_ms * 1e-3), 1),
+        out["hip_graph"] = {"ms_per_step": round(graph_ms, 4), "value": round(tokens / (graph_ms * 1e-3), 1),
                             "unit": "tokens/s", "note": "the same steps launched as replays of captured HIP graphs"}
-    if not args.no_at_scale and w.name != "large_cache_stress":
-        out["at_scale"] = at_scale(samkv)
+    layer0 = wb.layers_np[0]
+    del wb
+    torch.cuda.empty_cache()
+    if not args.no_secondary and w.name != "llama3_8b_layer":
+        w2 = synth.WORKLOADS["llama3_8b_layer"]
+        wb2 = Workbench(samkv, synth, w2, 0.15, 1, "per-layer", 1)
+        ms2, dom2, pk2 = wb2.run(200, 20)
+        out["secondary"] = {"workload": w2.name, "steps": 200, "warmup": 20, "ms_per_step": round(ms2, 4),
+                            "value": round(sum(w2.lens) / (ms2 * 1e-3), 1), "unit": "tokens/s", "m_total": wb2.m,
+                            "input_copies_rotated": wb2.n_rot, "dominant_call": dom2, "per_kernel": pk2,
+                            "note": "small single-layer workload: launch- and latency-bound, reported for context"}
+        g2 = wb2.graph_ms(200, 20)
+        if g2 is not None:
+            out["secondary"]["hip_graph_ms_per_step"] = round(g2, 4)
+        del wb2
+        torch.cuda.empty_cache()
+    if not args.no_sweep:
+        out["sweep"] = sweep(samkv, synth)
     if not args.no_cpu_baseline:
         rows = args.cpu_sample_rows or (m if m <= 2048 else 48)
-        out["cpu_baseline"] = cpu_baseline(layers_np[0], ratio, rows)
+        out["cpu_baseline"] = cpu_baseline(layer0, ratio, rows)
     print(json.dumps(out))
     return 0
 
