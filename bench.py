@@ -36,8 +36,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores, published
 FP32_VALU_PEAK_TFLOPS = 157.3
 RIDGE = MFMA_BF16_PEAK_TFLOPS / HBM_PEAK_GBS * 1e3   # flop per byte above which a bf16 kernel is MFMA-bound
 KERNELS = ("score", "select", "gather", "recompute_attn", "query_attn")          # the five entry points of the path
-STEP = ("score_select_gather", "recompute_attn", "query_attn")                   # what a step launches: the first three fused
+STEP = ("score_select_gather", "recompute_query_attn")                            # what a step launches: two fused calls
 EXTRA = ("score_select",)                                                        # also timed per call, outside the step
+ATTN_PAIR = "recompute_query_attn"
 
 
 def algorithmic_work(w, lens, m, n_q_tok):
@@ -60,6 +61,10 @@ def algorithmic_work(w, lens, m, n_q_tok):
                            "flops": 4 * hq * d * m * (m + 1) // 2},
         "query_attn": {"bytes": 2 * m * hkv * d * e + hq * n_q_tok * (d * e + (d + 1) * 4),
                        "flops": 4 * hq * d * n_q_tok * m},
+        # both attentions in one call: the sum of the two
+        "recompute_query_attn": {"bytes": (2 * hq + 2 * hkv) * m * d * e + hq * m * (d + 1) * 4
+                                          + 2 * m * hkv * d * e + hq * n_q_tok * (d * e + (d + 1) * 4),
+                                 "flops": 4 * hq * d * m * (m + 1) // 2 + 4 * hq * d * n_q_tok * m},
     }
 
 
@@ -89,25 +94,29 @@ def kernel_row(name, w, work, ms, layers_per_call=1):
 
 
 def read_traffic(workload, kernel: str):
-    """HBM bytes per launch (read + write) of a kernel, from the committed rocprofv3 --pmc summary of this
-    workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
-    prefixes = {"score": ["k_score<"], "select": ["k_select"], "gather": ["k_gather<"], "score_select": ["k_score_select"],
-                "score_select_gather": ["k_score_select"],
-                "recompute_attn": ["k_attn_%s<%d, true" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<true" % workload.dtype],
-                "query_attn": ["k_attn_%s<%d, false" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<false" % workload.dtype],
-                }[kernel]
+    """HBM bytes per launch (read + write) of a call's main kernel(s), from the committed rocprofv3 --pmc summary of
+    this workload (profiles/bench_<workload>.txt: FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy), or None."""
+    causal = ["k_attn_%s<%d, true" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<true" % workload.dtype]
+    plain = ["k_attn_%s<%d, false" % (workload.dtype, workload.head_dim), "k_attn_%s_dma<false" % workload.dtype]
+    groups = {"score": [["k_score<"]], "select": [["k_select"]], "gather": [["k_gather<"]],
+              "score_select": [["k_score_select"]], "score_select_gather": [["k_score_select"]],
+              "recompute_attn": [causal], "query_attn": [plain], "recompute_query_attn": [causal, plain]}[kernel]
     try:
         lines = open(os.path.join(ROOT, "profiles", f"bench_{workload.name}.txt")).read().splitlines()
     except OSError:
         return None
-    for line in lines:
-        if any(line.startswith(p) for p in prefixes):
-            try:
-                rd, wr = float(line.split()[-2]), float(line.split()[-1])
-                return (rd + wr) * 1e6
-            except ValueError:
-                return None
-    return None
+    total = 0.0
+    for prefixes in groups:
+        for line in lines:
+            if any(line.startswith(p) for p in prefixes):
+                try:
+                    total += (float(line.split()[-2]) + float(line.split()[-1])) * 1e6
+                except ValueError:
+                    return None
+                break
+        else:
+            return None
+    return total
 
 
 def cpu_baseline(layer, ratio, n_sample_rows, budget_s=30.0):
@@ -239,7 +248,11 @@ class Workbench:
         samkv = self.samkv
         to_dev = samkv.upload
         # ---- inputs: n_layers layers, replicated until the K/V working set passes 512 MB
-        self.layers_np = [synth.make_layer(w, l) for l in range(n_layers)]
+        self.layers_np = []
+        for l in range(n_layers):
+            self.layers_np.append(synth.make_layer(w, l))
+            if n_layers > 1 and l % 4 == 3:          # a long host-side phase: say that the run is alive
+                print(f"bench.py: {w.name}: layers 0..{l} drawn", file=sys.stderr, flush=True)
         kv_bytes = 2 * sum(w.lens) * w.n_kv_heads * w.head_dim * e * n_layers
         self.n_rot = max(1, min(16, math.ceil(512e6 / kv_bytes)))
         # Layout of a multi-layer workload.  "stacked": every document's cache holds all layers, [(layer, KV head)][L][d],
@@ -286,6 +299,8 @@ class Workbench:
                                                               b.cu_k_dev, b.ws),
             "score_select_gather": lambda s, b: S.samkv_score_select_gather(s["caches"], s["q_tok"], s["q_loc"], ratio, 0, 0,
                                                                             None, b.idx, b.cu_k_dev, b.k_c, b.v_c, b.ws),
+            "recompute_query_attn": lambda s, b: S.samkv_recompute_query_attn(s["q_rec"], s["q_tok"], b.k_c, b.v_c, scale,
+                                                                              b.rec_out, b.rec_lse, b.q_out, b.q_lse, b.ws),
         }
         self.work = algorithmic_work(w, w.lens, m, w.n_q_tok)
 
@@ -408,7 +423,7 @@ def sweep(samkv, synth, iters=30, warmup=8):
     import numpy as np
     import torch
     w = synth.WORKLOADS["mistral_7b_sweep"]
-    names = KERNELS + ("score_select_gather",)
+    names = KERNELS + STEP
     rows, first = [], None
     for ratio in w.ratios:
         wb = Workbench(samkv, synth, w, ratio, 1, "per-layer", 1, caches_from=first)
@@ -503,9 +518,15 @@ def main() -> int:
     roof["avg_launch_ms"] = per_kernel[dom]["ms"]
     roof["traffic"] = read_traffic(w, dom)
     roof["algorithmic"] = (work[dom]["flops"] if bound != "hbm" else work[dom]["bytes"]) * wb.layers_per_call
-    if dom.endswith("attn") and w.dtype == "bf16":
-        roof["note"] = ("the call = two small launches that rewrite V as scaled half precision (not counted as "
-                        "algorithmic work) + the attention kernel; achieved = algorithmic flop / duration of the call")
+    if dom == ATTN_PAIR:
+        rec, qry = per_kernel["recompute_attn"], per_kernel["query_attn"]
+        roof["note"] = ("the dominant call runs both attentions: the launches that rewrite V as scaled half precision "
+                        "(not counted as algorithmic work), the causal kernel, the query kernel and its merge; "
+                        "achieved = algorithmic flop of both attentions / duration of the call")
+        roof["components"] = {"recompute_attn": {"ms_as_a_separate_call": rec["ms"], "TFLOP/s": rec["TFLOP/s"],
+                                                 "frac": rec["frac"], "flop": work["recompute_attn"]["flops"] * wb.layers_per_call},
+                              "query_attn": {"ms_as_a_separate_call": qry["ms"], "TFLOP/s": qry["TFLOP/s"], "bound": qry["bound"],
+                                             "frac": qry["frac"], "flop": work["query_attn"]["flops"] * wb.layers_per_call}}
 
     tokens = sum(w.lens) * n_layers
     out = {
@@ -524,7 +545,7 @@ def main() -> int:
                    "input_copies_rotated": wb.n_rot, "streams": wb.n_streams,
                    "layout": "stacked: one call per entry point serves all layers" if wb.stacked else "per-layer calls",
                    "step": "samkv_score_select_gather (scores = NULL: the scores stay on chip, only the kept positions "
-                           "and the compacted rows are written), samkv_recompute_attn, samkv_query_attn",
+                           "and the compacted rows are written), samkv_recompute_query_attn (both attentions, V prepared once)",
                    "inputs": "seeded synthetic caches (synth.make_layer), resident in HBM"},
         "per_kernel": per_kernel,
         "roofline": roof,

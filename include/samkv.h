@@ -288,6 +288,16 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
                      int32_t dtype, float scale, float* out, float* lse, void* ws, size_t ws_bytes,
                      void* stream);
 
+/* samkv_recompute_attn followed by samkv_query_attn over the same compacted cache, as one call (Sec. 3.3: the kept
+ * tokens are recomputed, then the query is prefilled over the result; here both read k_c, v_c as they stand).  The
+ * half-precision copy of V that the bf16 kernels read is made once and serves both; results are bit-identical to
+ * the two calls.  Arguments as in the two calls; ws as for samkv_query_attn.  A caller that updates the cache between
+ * the two attentions (samkv_kv_update) uses the separate calls. */
+int samkv_recompute_query_attn(const void* q_rec, const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
+                               int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                               float scale, float* rec_out, float* rec_lse, float* q_out, float* q_lse, void* ws,
+                               size_t ws_bytes, void* stream);
+
 /* The same prefill with the query's own keys and values: query token t attends to the whole compacted
  * cache and to query tokens 0..t (itself included), which is what an incremental prefill of the query
  * after the cached documents computes (Sec. 3.3, last paragraph).

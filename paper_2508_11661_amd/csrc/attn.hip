@@ -864,10 +864,9 @@ hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
 
 template <bool CAUSAL>
 hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
-  constexpr int LDS = kDmaLdsBytes;
   AttnArgs a = make_args(l);
   dim3 grid = attn_grid(&a, (l.rows + 255) / 256);
-  hipLaunchKernelGGL((k_attn_bf16_dma<CAUSAL>), grid, dim3(512), LDS, s, a);
+  hipLaunchKernelGGL((k_attn_bf16_dma<CAUSAL>), grid, dim3(512), kDmaLdsBytes, s, a);
   return hipGetLastError();
 }
 

@@ -723,6 +723,40 @@ int samkv_peak_read(const void* src, size_t bytes, void* sink, void* stream) {
   return dev(launch_peak_read(src, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)));
 }
 
+// The two attention problems of the path as launch descriptions (V not yet prepared).
+static AttnLaunch recompute_launch(const void* q_rec, const void* k_c, const void* v_c, int m_total, int hq, int hkv, int d,
+                                   int dtype, float scale, float* out, float* lse) {
+  AttnLaunch a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.d = d; a.causal = 1;
+  a.n_batch = hq; a.batch_per_kv = hq / hkv; a.rows = m_total; a.m = m_total;
+  a.q = q_rec; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
+  a.n_split = 1; a.chunk = m_total;
+  return a;
+}
+
+// q_tok [Hq][Lq][d] is, per KV head, one contiguous block of G*Lq rows that all read the same K/V.
+static AttnLaunch query_launch(const void* q_tok, int n_q_tok, const void* k_c, const void* v_c, int m_total, int hq, int hkv,
+                               int d, int dtype, float scale, float* out, float* lse, const SplitPlan& p, void* ws) {
+  AttnLaunch a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.d = d; a.causal = 0;
+  a.n_batch = hkv; a.batch_per_kv = 1; a.rows = (hq / hkv) * n_q_tok; a.m = m_total;
+  a.q = q_tok; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
+  a.n_split = p.n_split; a.chunk = p.chunk;
+  if (p.n_split > 1) {
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o);
+    a.part_lse = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_lse);
+  }
+  return a;
+}
+
+static hipError_t run_attn(const AttnLaunch& a, hipStream_t s) {
+  hipError_t e = a.dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  if (e == hipSuccess && !a.causal && a.n_split > 1) e = launch_attn_merge(a, s);
+  return e;
+}
+
 int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, int32_t m_total, int32_t n_q_heads,
                          int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float scale, float* out, float* lse,
                          void* ws, size_t ws_bytes, void* stream) {
@@ -730,15 +764,10 @@ int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, in
   if (rc != SAMKV_OK) return rc;
   const AttnWs w = attn_ws(dtype, true, n_kv_heads, 0, m_total, head_dim);
   if (w.bytes > 0 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes)) return SAMKV_EWORKSPACE;
-  AttnLaunch a;
-  memset(&a, 0, sizeof(a));
-  a.dtype = dtype; a.d = head_dim; a.causal = 1;
-  a.n_batch = n_q_heads; a.batch_per_kv = n_q_heads / n_kv_heads; a.rows = m_total; a.m = m_total;
-  a.q = q_rec; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
-  a.n_split = 1; a.chunk = m_total;
+  AttnLaunch a = recompute_launch(q_rec, k_c, v_c, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = prepare_v(&a, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
-  if (e == hipSuccess) e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
+  if (e == hipSuccess) e = run_attn(a, s);
   return dev(e);
 }
 
@@ -747,25 +776,37 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
                      float* lse, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_attn(q_tok, k_c, v_c, n_q_tok, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse);
   if (rc != SAMKV_OK) return rc;
-  // q_tok [Hq][Lq][d] is, per KV head, one contiguous block of G*Lq rows that all read the same K/V.
-  const int rows = (n_q_heads / n_kv_heads) * n_q_tok;
-  const AttnWs w = attn_ws(dtype, false, n_kv_heads, rows, m_total, head_dim);
-  const SplitPlan& p = w.split;
+  const AttnWs w = attn_ws(dtype, false, n_kv_heads, (n_q_heads / n_kv_heads) * n_q_tok, m_total, head_dim);
   if (w.bytes > 0 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes)) return SAMKV_EWORKSPACE;
-  AttnLaunch a;
-  memset(&a, 0, sizeof(a));
-  a.dtype = dtype; a.d = head_dim; a.causal = 0;
-  a.n_batch = n_kv_heads; a.batch_per_kv = 1; a.rows = rows; a.m = m_total;
-  a.q = q_tok; a.k = k_c; a.v = v_c; a.out = out; a.lse = lse; a.scale = scale;
-  a.n_split = p.n_split; a.chunk = p.chunk;
-  if (p.n_split > 1) {
-    a.part_o = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_o);
-    a.part_lse = reinterpret_cast<float*>(static_cast<char*>(ws) + p.part_lse);
-  }
+  AttnLaunch a = query_launch(q_tok, n_q_tok, k_c, v_c, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, out, lse,
+                              w.split, ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = prepare_v(&a, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
-  if (e == hipSuccess) e = dtype == SAMKV_BF16 ? launch_attn_bf16(a, s) : launch_attn_f32(a, s);
-  if (e == hipSuccess && p.n_split > 1) e = launch_attn_merge(a, s);
+  if (e == hipSuccess) e = run_attn(a, s);
+  return dev(e);
+}
+
+int samkv_recompute_query_attn(const void* q_rec, const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
+                               int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                               float scale, float* rec_out, float* rec_lse, float* q_out, float* q_lse, void* ws,
+                               size_t ws_bytes, void* stream) {
+  int rc = check_attn(q_rec, k_c, v_c, m_total, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, rec_out, rec_lse);
+  if (rc != SAMKV_OK) return rc;
+  rc = check_attn(q_tok, k_c, v_c, n_q_tok, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, q_out, q_lse);
+  if (rc != SAMKV_OK) return rc;
+  // the workspace of the query attention holds the prepared V behind its key-chunk partials; the causal attention
+  // needs nothing else, so one preparation serves both
+  const AttnWs w = attn_ws(dtype, false, n_kv_heads, (n_q_heads / n_kv_heads) * n_q_tok, m_total, head_dim);
+  if (w.bytes > 0 && (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < w.bytes)) return SAMKV_EWORKSPACE;
+  AttnLaunch rec = recompute_launch(q_rec, k_c, v_c, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, rec_out, rec_lse);
+  AttnLaunch qry = query_launch(q_tok, n_q_tok, k_c, v_c, m_total, n_q_heads, n_kv_heads, head_dim, dtype, scale, q_out,
+                                q_lse, w.split, ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = prepare_v(&rec, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
+  qry.v = rec.v;
+  qry.v_unscale = rec.v_unscale;
+  if (e == hipSuccess) e = run_attn(rec, s);
+  if (e == hipSuccess) e = run_attn(qry, s);
   return dev(e);
 }
 

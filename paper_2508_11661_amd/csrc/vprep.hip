@@ -10,6 +10,9 @@
 //   k_v_absmax   largest |v| per (KV head, row chunk), as the integer bit pattern of the bf16 magnitude
 //   k_v_to_f16   reduces a head's chunk maxima (every workgroup of the head does so redundantly), converts its own
 //                row chunk, and workgroup 0 of the head writes the factor that undoes the scale
+// Heads of at most kOneLaunchPieces 16-byte pieces (short compacted caches, where a launch costs more than the work)
+// take ONE launch instead: k_v_prep_small, a few large workgroups per head, each of which finds the head's maximum
+// itself (the head is read from L2 a few times over) and converts its share.
 #include "common.hpp"
 
 namespace samkv {
@@ -73,6 +76,51 @@ __global__ __launch_bounds__(NT) void k_v_to_f16(const u32x4* __restrict__ v, co
   }
 }
 
+// One launch for short heads: workgroup (c, g) scans ALL of head g for its largest magnitude, then converts chunk c.
+constexpr int NT1 = 1024;
+__global__ __launch_bounds__(NT1) void k_v_prep_small(const u32x4* __restrict__ v, u32x4* __restrict__ v16,
+                                                      float* __restrict__ unscale, int total, int per) {
+  __shared__ uint32_t lds[NT1 / 64];
+  const int c = blockIdx.x, g = blockIdx.y;
+  const u32x4* src = v + (size_t)g * total;
+  uint32_t mx = 0;
+  constexpr int U = 8;   // loads in flight per thread: a head of 512 KB is four round trips
+  for (int i = threadIdx.x; i < total; i += U * NT1) {
+    u32x4 w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) w[u] = src[min(i + u * NT1, total - 1)];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) mx = max(mx, max(w[u][e] & 0x7FFFu, (w[u][e] >> 16) & 0x7FFFu));
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off));
+  if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = lds[0];
+#pragma unroll
+  for (int wv = 1; wv < NT1 / 64; ++wv) mx = max(mx, lds[wv]);
+  const int expo = (int)(mx >> 7) & 0xFF;
+  int shift = expo == 0 ? 0 : 14 - (expo - 127);
+  shift = max(-113, min(113, shift));
+  if (c == 0 && threadIdx.x == 0) unscale[g] = __builtin_ldexpf(1.0f, -shift);
+  u32x4* dst = v16 + (size_t)g * total;
+  const int begin = c * per, end = min(total, begin + per);
+  for (int i = begin + threadIdx.x; i < end; i += NT1) {
+    const u32x4 w = src[i];
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const f16x2 h = {(_Float16)__builtin_ldexpf(bf16_lo(w[e]), shift), (_Float16)__builtin_ldexpf(bf16_hi(w[e]), shift)};
+      o[e] = __builtin_bit_cast(uint32_t, h);
+    }
+    dst[i] = o;
+  }
+}
+
+constexpr long long kOneLaunchPieces = 32768;  // 512 KB per head
+
 }  // namespace
 
 int v_prep_chunks(int n_kv, int m) {
@@ -85,6 +133,13 @@ int v_prep_chunks(int n_kv, int m) {
 
 hipError_t launch_v_prep(const void* v, int n_kv, int m, int d, void* v16, uint32_t* part, float* unscale, hipStream_t s) {
   const long long total = (long long)m * d * 2 / 16;  // 16-byte pieces per head
+  if (total <= kOneLaunchPieces) {
+    const int c1 = (int)((total + 8191) / 8192);         // a chunk converts up to 128 KB
+    const int per1 = (int)((total + c1 - 1) / c1);
+    hipLaunchKernelGGL(k_v_prep_small, dim3(c1, n_kv), dim3(NT1), 0, s, static_cast<const u32x4*>(v),
+                       static_cast<u32x4*>(v16), unscale, (int)total, per1);
+    return hipGetLastError();
+  }
   const int n_chunks = v_prep_chunks(n_kv, m);
   const long long per = (total + n_chunks - 1) / n_chunks;
   const dim3 grid(n_chunks, n_kv);

@@ -21,7 +21,7 @@ EXPORTS = ("samkv_strerror", "samkv_kept_count", "samkv_kept_count_mid", "samkv_
            "samkv_score", "samkv_score_noalloc", "samkv_score_select", "samkv_score_select_gather", "samkv_topk_select", "samkv_topk_select_v", "samkv_gather_v",
            "samkv_gather_q_v", "samkv_block_scores", "samkv_block_workspace_bytes", "samkv_block_select",
            "samkv_block_select_filter", "samkv_block_filter_count", "samkv_block_select_count", "samkv_gather_g", "samkv_gather_q_g",
-           "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_query_attn_self",
+           "samkv_gather", "samkv_gather_q", "samkv_recompute_attn", "samkv_query_attn", "samkv_recompute_query_attn", "samkv_query_attn_self",
            "samkv_kv_update", "samkv_peak_mfma_bf16", "samkv_peak_mfma_bf16_data", "samkv_peak_copy", "samkv_peak_read")
 SAMKV_OVERWRITE, SAMKV_FUSION = 0, 1
 
@@ -92,6 +92,8 @@ def _load() -> ctypes.CDLL:
     lib.samkv_recompute_attn.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_query_attn.restype = ctypes.c_int
     lib.samkv_query_attn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.samkv_recompute_query_attn.restype = ctypes.c_int
+    lib.samkv_recompute_query_attn.argtypes = [vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.samkv_query_attn_self.restype = ctypes.c_int
     lib.samkv_query_attn_self.argtypes = [vp, i32, vp, vp, i32, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
     lib.samkv_peak_mfma_bf16.restype = ctypes.c_int
@@ -428,6 +430,24 @@ def samkv_query_attn(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, 
            "samkv_query_attn")
 
 
+def samkv_recompute_query_attn(q_rec: torch.Tensor, q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor,
+                               scale: float, rec_out: torch.Tensor, rec_lse: torch.Tensor, q_out: torch.Tensor,
+                               q_lse: torch.Tensor, ws: Optional[torch.Tensor]) -> None:
+    """samkv_recompute_attn and samkv_query_attn over the same compacted cache in one call (V prepared once)."""
+    hq, m, d = q_rec.shape
+    lq = int(q_tok.shape[1])
+    hkv = k_c.shape[0]
+    assert k_c.shape == (hkv, m, d) and v_c.shape == (hkv, m, d) and tuple(q_tok.shape) == (hq, lq, d)
+    assert tuple(rec_out.shape) == (hq, m, d) and tuple(rec_lse.shape) == (hq, m)
+    assert tuple(q_out.shape) == (hq, lq, d) and tuple(q_lse.shape) == (hq, lq)
+    for x in (rec_out, rec_lse, q_out, q_lse):
+        assert x.dtype == torch.float32
+    _check(_lib.samkv_recompute_query_attn(_ptr(q_rec), _ptr(q_tok), lq, _ptr(k_c), _ptr(v_c), m, hq, hkv, d,
+                                           _dtype_code(q_rec.dtype), scale, _ptr(rec_out), _ptr(rec_lse), _ptr(q_out),
+                                           _ptr(q_lse), _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
+                                           _stream()), "samkv_recompute_query_attn")
+
+
 def samkv_query_attn_self(q_tok: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, k_self: torch.Tensor,
                           v_self: torch.Tensor, scale: float, out: torch.Tensor, lse: torch.Tensor,
                           ws: torch.Tensor) -> None:
@@ -492,7 +512,8 @@ def hot_path(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor],
              ratio: float, scale: float, buf: LayerBuffers, n_sink: int = 0, n_local: int = 0,
              fused: bool = True) -> None:
     """One pass of the whole hot path of a layer: score, select, gather, recompute, query attention.  `fused`
-    scores, selects and compacts in one call (same kept positions, same bytes); otherwise the three separate calls."""
+    scores, selects and compacts in one call and runs both attentions in one call (same kept positions, same bits);
+    otherwise the five separate calls."""
     if fused:
         samkv_score_select_gather(caches, q_tok, q_loc, ratio, n_sink, n_local, buf.scores, buf.idx, buf.cu_k_dev,
                                   buf.k_c, buf.v_c, buf.ws)
@@ -500,5 +521,9 @@ def hot_path(caches: Caches, q_tok: torch.Tensor, q_loc: Optional[torch.Tensor],
         samkv_score(caches, q_tok, q_loc, buf.scores, buf.ws)
         samkv_topk_select(buf.scores, caches, ratio, n_sink, n_local, buf.idx, buf.cu_k_dev, buf.ws)
         samkv_gather(caches, buf.idx, ratio, buf.k_c, buf.v_c)
-    samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws)
-    samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws)
+    if fused:
+        samkv_recompute_query_attn(q_rec, q_tok, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.q_out, buf.q_lse,
+                                   buf.ws)
+    else:
+        samkv_recompute_attn(q_rec, buf.k_c, buf.v_c, scale, buf.rec_out, buf.rec_lse, buf.ws)
+        samkv_query_attn(q_tok, buf.k_c, buf.v_c, scale, buf.q_out, buf.q_lse, buf.ws)

@@ -195,6 +195,12 @@ def test_argument_errors_are_reported_before_any_launch(S):
     misaligned._keep[1][1] = 0x1008
     assert L.samkv_score(ctypes.byref(misaligned), fake, 4, None, 0, fake, fake, 1 << 20, None) == -1
     assert L.samkv_query_attn(fake, 0, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -1
+    pair = lambda *x: L.samkv_recompute_query_attn(*x)
+    assert pair(fake, None, 4, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, fake, fake, fake, 1 << 30, None) == -1
+    assert pair(fake, fake, 4, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, None, fake, fake, 1 << 30, None) == -1
+    assert pair(fake, fake, 0, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, fake, fake, fake, 1 << 30, None) == -1
+    assert pair(fake, fake, 4, fake, fake, 64, 4, 2, 128, 1, 0.1, fake, fake, fake, fake, None, 0, None) == -3
+    assert pair(fake, fake, 4, fake, fake, 64, 4, 2, 96, 1, 0.1, fake, fake, fake, fake, fake, 1 << 30, None) == -2
     assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, None, fake, 4, 2, 128, 1, 0.1, fake, fake, fake, 1 << 30, None) == -1
     assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, fake, fake, 4, 2, 128, 1, 0.1, fake, fake, None, 0, None) == -3
     assert L.samkv_query_attn_self(fake, 4, fake, fake, 64, fake, fake, 4, 2, 128, 1, 0.1, fake, fake, fake, 64, None) == -3
