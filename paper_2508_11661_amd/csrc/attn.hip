@@ -235,7 +235,8 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
     const bool more = tile + 1 < n_tiles;
     if (more) load_tile(tile + 1);
 
-    const bool active = (!CAUSAL || k0 <= wave_last) && (KG == 1 || k0 < kv_end);
+    // a wave whose rows all lie past the last row (ragged last row tile) only helps with the tile traffic
+    const bool active = wave_first < a.rows && (!CAUSAL || k0 <= wave_last) && (KG == 1 || k0 < kv_end);
     if (active) {
       const char* sk = smem + (tile & 1) * C::TILE_BYTES + kg * C::BK * C::KSTR;
       const char* sv = smem + (tile & 1) * C::TILE_BYTES + C::BKT * C::KSTR + kg * C::BK * C::VSTR;
@@ -442,11 +443,15 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   const int r = q0 + wave * 32 + rw;
   const int r_c = min(r, a.rows - 1);
   const int wave_first = q0 + wave * 32;
-  // Without a mask every tile but a ragged last one is full: n_full = span / BK.  It is written as a
-  // per-wave quantity on purpose (the first operand of the min is always the larger one): with a
-  // workgroup-uniform bound the compiler re-versions the step loop and spills registers.
-  const int n_full = CAUSAL ? min((wave_first + 1) / BK, span / BK) : min((wave_first + (1 << 24)) / BK, span / BK);
-  const bool has_tail = n_full * BK < span;
+  // A wave whose rows all lie past the last row (the ragged last row tile of a problem: 4120 rows are 16 tiles and
+  // 24 rows) computes nothing: no full tiles, no tail.  It still sends its share of the tile requests and meets the
+  // barriers.  The last row tile is the one with the longest key range, so this is the most expensive workgroup of
+  // every head, and its SIMDs are left to the waves that have rows.
+  const bool has_rows = wave_first < a.rows;
+  const int n_full = !has_rows ? 0
+                     : CAUSAL  ? min((wave_first + 1) / BK, span / BK)
+                               : min((wave_first + (1 << 24)) / BK, span / BK);
+  const bool has_tail = has_rows && n_full * BK < span;
 
   bf16x8 bq[ND];
   {

@@ -7,8 +7,6 @@
 //   k_qtilde  Eq. 1 for the query heads of a KV group, folded into one vector per document (the mean
 //             over the group is linear, so one pass over K serves all heads of the group).
 //   k_score   streams K once.  HBM-bound: d*e bytes read and 4 bytes written per token and KV head.
-#include <stdlib.h>
-
 #include "common.hpp"
 #include "kernels_core.hpp"
 
@@ -302,8 +300,7 @@ hipError_t run_prologue(const ScoreLaunch& a, hipStream_t s, QuerySrc* out) {
   const bool bias = a.q_loc != nullptr && a.n_ctx > 1;
   // bytes of Q rows that pass through one query head's workgroup in the one-launch prologue
   const size_t per_head = ((size_t)a.n_q_tok + (bias ? (size_t)a.n_ctx * a.w_loc : 0)) * D * (BF16 ? 2 : 4);
-  static const size_t one_launch_bytes = getenv("SAMKV_PROLOGUE_BYTES") ? (size_t)atol(getenv("SAMKV_PROLOGUE_BYTES")) : (1u << 20);  // TEMP
-  if (a.n_ctx <= 64 && per_head <= one_launch_bytes) {
+  if (a.n_ctx <= 64 && per_head <= (1u << 20)) {
     const size_t lds = (size_t)(2 * D + 16 * D + SAMKV_MAX_CTX + a.n_ctx * D) * sizeof(float);
     hipLaunchKernelGGL((k_prologue<BF16, D>), dim3(a.hq), dim3(1024), lds, s, a.q_tok, a.n_q_tok, a.q_loc, a.w_loc, a.n_ctx,
                        a.hq, bias ? 1 : 0, a.ws_loc);

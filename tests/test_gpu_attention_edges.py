@@ -37,6 +37,9 @@ def _rows(m, n, seed):
     # few workgroups and more than 256 rows: the variant whose two key groups split every 128-key step
     ("bf16", 128, 32, 8, 1540), ("bf16", 128, 4, 2, 257), ("bf16", 128, 4, 4, 321), ("bf16", 64, 16, 4, 449),
     ("bf16", 128, 2, 1, 385), ("bf16", 64, 2, 2, 2048),
+    # enough row tiles for the asynchronous-load kernel, whose workgroups hold the 2, 4 or 8 query heads of a KV head:
+    # two heads per KV head, and a KV head count that is not a multiple of eight
+    ("bf16", 128, 48, 24, 2300), ("bf16", 128, 40, 10, 2600),
 ])
 def test_recompute_attention_shapes(dtype, d, hq, hkv, m):
     import torch
