@@ -66,11 +66,15 @@ __global__ __launch_bounds__(256) void k_pool(const void* q_tok, int n_q_tok, co
 
 // One block per query head h.  Step 1: w_j[h] = |cos(Q_que[h], Q_loc_j[h])| for every document j (one
 // wave per j, butterfly sums).  Step 2: bias[h][c] = sum_j w_j[h] Q_loc_j[h][c]; thread (channel c,
-// slice s) adds the documents j = s, s + NS, ..., and the slices meet in LDS in a fixed order.
-__global__ __launch_bounds__(1024) void k_bias(const float* que, const float* loc, float* wgt, float* bias, int n_ctx,
+// slice s) adds the documents j = s, s + NS, ..., and the slices meet in LDS in a fixed order.  Step 3: Eq. 1 per
+// query head, Q^_i[h] = Q_que[h] + (bias[h] - w_i Q_loc_i[h]) / (N - 1), written over Q_loc_i[h] in place (thread
+// (c, s) is the only one that still touches element c of the documents of its slice), so that `loc` leaves as
+// qhat[i][h][:] like the output of k_prologue and k_score folds the heads of a KV group.
+__global__ __launch_bounds__(1024) void k_bias(const float* que, float* loc, float* wgt, float* bias, int n_ctx,
                                                int hq, int d) {
   __shared__ float red[1024];
   __shared__ float w_s[SAMKV_MAX_CTX];
+  __shared__ float b_s[128];
   const int h = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   for (int j = wave; j < n_ctx; j += 16) {
     float dot = 0.f, na = 0.f, nb = 0.f;
@@ -100,6 +104,13 @@ __global__ __launch_bounds__(1024) void k_bias(const float* que, const float* lo
     float b = 0.f;
     for (int s2 = 0; s2 < ns; ++s2) b += red[s2 * d + c];
     bias[h * d + c] = b;
+    b_s[c] = b;
+  }
+  __syncthreads();
+  const float q = que[h * d + c], b = b_s[c], inv = 1.f / (float)(n_ctx - 1);
+  for (int j = sl; j < n_ctx; j += ns) {
+    float* p = loc + ((size_t)j * hq + h) * d + c;
+    *p = q + (b - w_s[j] * *p) * inv;
   }
 }
 
@@ -309,8 +320,12 @@ hipError_t run_prologue(const ScoreLaunch& a, hipStream_t s, QuerySrc* out) {
   }
   hipLaunchKernelGGL((k_pool<BF16, D>), dim3(a.hq, bias ? a.n_ctx + 1 : 1), dim3(256), 0, s, a.q_tok, a.n_q_tok,
                      a.q_loc, a.w_loc, a.hq, a.ws_que, a.ws_loc);
-  if (bias)
+  if (bias) {
+    // two launches: the pooled local caches leave k_bias as Eq. 1 per query head, folded by the score kernel
     hipLaunchKernelGGL(k_bias, dim3(a.hq), dim3(1024), 0, s, a.ws_que, a.ws_loc, a.ws_w, a.ws_base, a.n_ctx, a.hq, D);
+    out->q = a.ws_loc; out->heads = a.hq; out->group = a.hq / a.hkv;
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(k_qtilde, dim3(a.n_ctx, a.hkv), dim3(D), 0, s, a.ws_que, a.ws_base, a.ws_loc, a.ws_w, a.ws_qt,
                      a.n_ctx, a.hq, a.hkv, D, bias ? 1 : 0);
   out->q = a.ws_qt; out->heads = a.hkv; out->group = 1;

@@ -78,13 +78,14 @@ __global__ __launch_bounds__(NT) void k_v_to_f16(const u32x4* __restrict__ v, co
 
 // One launch for short heads: workgroup (c, g) scans ALL of head g for its largest magnitude, then converts chunk c.
 constexpr int NT1 = 1024;
+constexpr int kSmallChunk = 2048;   // 16-byte pieces converted per workgroup (32 KB)
 __global__ __launch_bounds__(NT1) void k_v_prep_small(const u32x4* __restrict__ v, u32x4* __restrict__ v16,
                                                       float* __restrict__ unscale, int total, int per) {
   __shared__ uint32_t lds[NT1 / 64];
   const int c = blockIdx.x, g = blockIdx.y;
   const u32x4* src = v + (size_t)g * total;
   uint32_t mx = 0;
-  constexpr int U = 8;   // loads in flight per thread: a head of 512 KB is four round trips
+  constexpr int U = 16;  // loads in flight per thread: a head of 512 KB is two round trips
   for (int i = threadIdx.x; i < total; i += U * NT1) {
     u32x4 w[U];
 #pragma unroll
@@ -107,15 +108,20 @@ __global__ __launch_bounds__(NT1) void k_v_prep_small(const u32x4* __restrict__ 
   if (c == 0 && threadIdx.x == 0) unscale[g] = __builtin_ldexpf(1.0f, -shift);
   u32x4* dst = v16 + (size_t)g * total;
   const int begin = c * per, end = min(total, begin + per);
-  for (int i = begin + threadIdx.x; i < end; i += NT1) {
-    const u32x4 w = src[i];
+  // a chunk is at most kSmallChunk pieces: both loads of a thread are in flight together
+  u32x4 w[kSmallChunk / NT1];
+#pragma unroll
+  for (int u = 0; u < kSmallChunk / NT1; ++u) w[u] = src[min(begin + (int)threadIdx.x + u * NT1, total - 1)];
+#pragma unroll
+  for (int u = 0; u < kSmallChunk / NT1; ++u) {
+    const int i = begin + (int)threadIdx.x + u * NT1;
     u32x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const f16x2 h = {(_Float16)__builtin_ldexpf(bf16_lo(w[e]), shift), (_Float16)__builtin_ldexpf(bf16_hi(w[e]), shift)};
+      const f16x2 h = {(_Float16)__builtin_ldexpf(bf16_lo(w[u][e]), shift), (_Float16)__builtin_ldexpf(bf16_hi(w[u][e]), shift)};
       o[e] = __builtin_bit_cast(uint32_t, h);
     }
-    dst[i] = o;
+    if (i < end) dst[i] = o;
   }
 }
 
@@ -134,8 +140,8 @@ int v_prep_chunks(int n_kv, int m) {
 hipError_t launch_v_prep(const void* v, int n_kv, int m, int d, void* v16, uint32_t* part, float* unscale, hipStream_t s) {
   const long long total = (long long)m * d * 2 / 16;  // 16-byte pieces per head
   if (total <= kOneLaunchPieces) {
-    const int c1 = (int)((total + 8191) / 8192);         // a chunk converts up to 128 KB
-    const int per1 = (int)((total + c1 - 1) / c1);
+    const int c1 = (int)((total + kSmallChunk - 1) / kSmallChunk);
+    const int per1 = kSmallChunk;
     hipLaunchKernelGGL(k_v_prep_small, dim3(c1, n_kv), dim3(NT1), 0, s, static_cast<const u32x4*>(v),
                        static_cast<u32x4*>(v16), unscale, (int)total, per1);
     return hipGetLastError();
