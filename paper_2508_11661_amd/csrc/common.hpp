@@ -105,7 +105,7 @@ hipError_t launch_gather_q(const GatherLaunch& a, const PtrTable& q, const IntTa
 #endif
 inline int attn_bf16_waves(int causal, int n_batch, int rows) {
   if (causal) return (long long)n_batch * ((rows + 255) / 256) >= SAMKV_WAVE8_MIN_TILES ? 8 : 4;
-  return rows >= 1024 ? 8 : 4;
+  return rows >= 512 ? 8 : 4;   // not causal: from two 256-row tiles per KV head on (measured at 256 / 512 / 1024 rows)
 }
 
 // One attention problem: `n_batch` independent row blocks, batch b reads KV head b / batch_per_kv.

@@ -117,7 +117,10 @@ SplitPlan plan_splits(int dtype, int n_batch, int rows, int m, int d) {
   const int bk = dtype == SAMKV_BF16 ? 64 : 32;
   const long long base = (long long)((rows + bq - 1) / bq) * n_batch;
   const int key_tiles = (m + bk - 1) / bk;
-  long long want = (512 + base - 1) / base;  // aim at ~2 workgroups per compute unit
+  // aim at as many workgroups as are resident at once: one per compute unit for the eight-wave kernel (256 rows),
+  // two for the four-wave one; a second round of workgroups only adds partial results to merge
+  const int wg_target = bq == 256 ? 256 : 512;
+  long long want = (wg_target + base - 1) / base;
   if (want > 64) want = 64;
   if (want < 1) want = 1;
   int tiles_per = (int)((key_tiles + want - 1) / want);
