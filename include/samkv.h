@@ -293,9 +293,14 @@ int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const 
 
 /* samkv_recompute_attn followed by samkv_query_attn over the same compacted cache, as one call (Sec. 3.3: the kept
  * tokens are recomputed, then the query is prefilled over the result; here both read k_c, v_c as they stand).  The
- * half-precision copy of V that the bf16 kernels read is made once and serves both; results are bit-identical to
- * the two calls.  Arguments as in the two calls; ws as for samkv_query_attn.  A caller that updates the cache between
- * the two attentions (samkv_kv_update) uses the separate calls. */
+ * half-precision copy of V that the bf16 kernels read is made once and serves both.  bf16: both attentions run in ONE
+ * kernel launch; the query attention's workgroups are handed out first and each walks all keys of its rows in one
+ * chunk (no partial results, no merge), which takes as long as the causal problem's longest row tile, so the query
+ * attention hides inside the causal one.  The recompute outputs are bit-identical to samkv_recompute_attn's; the query
+ * outputs follow the same definition as samkv_query_attn's but sum the keys in one chunk instead of several, so they
+ * agree with it to rounding (both within the stated precision), not bit for bit.  float32: the two kernels one after
+ * the other, bit-identical to the two calls.  Arguments as in the two calls; ws as for samkv_query_attn.  A caller
+ * that updates the cache between the two attentions (samkv_kv_update) uses the separate calls. */
 int samkv_recompute_query_attn(const void* q_rec, const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
                                int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
                                float scale, float* rec_out, float* rec_lse, float* q_out, float* q_lse, void* ws,

@@ -98,11 +98,14 @@ __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&o)[D / 32], fl
 // before the next group starts.  With 8 KV heads there is one group and this is "KV head = x % 8, all row tiles in
 // longest-first order"; with many KV heads (several layers stacked as heads) an XCD still streams one head at a
 // time instead of dozens.  kv_groups == 0 (head count not a multiple of 8): plain x = batch, y = tile.
-__device__ __forceinline__ void map_block(const AttnArgs& a, bool causal, int* kvh, int* batch, int* tile) {
-  const int x = blockIdx.x, y = blockIdx.y;
+// A workgroup's coordinates in the (batch, row tile, key chunk) grid of its problem: a plain launch takes them from
+// the hardware, the pair launch below hands out two problems' grids from one linear index
+// (x, y, z of grid_y rows): plain ints, so that nothing of it ever lives in memory.
+__device__ __forceinline__ void map_block(const AttnArgs& a, bool causal, int x, int y, int grid_y, int* kvh, int* batch,
+                                          int* tile) {
   int ty;
   if (a.kv_groups > 0) {
-    const int tiles = gridDim.y / a.kv_groups;
+    const int tiles = grid_y / a.kv_groups;
     const int grp = y / tiles;
     ty = y - grp * tiles;
     *kvh = grp * 8 + (x & 7);
@@ -112,7 +115,7 @@ __device__ __forceinline__ void map_block(const AttnArgs& a, bool causal, int* k
     const int n_kv = a.n_batch / a.batch_per_kv;
     *kvh = x % n_kv;
     *batch = *kvh * a.batch_per_kv + x / n_kv;
-    *tile = causal ? (int)gridDim.y - 1 - y : y;
+    *tile = causal ? grid_y - 1 - y : y;
   }
 }
 
@@ -140,7 +143,7 @@ struct Bf16Cfg {
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 template <int D, bool CAUSAL, int NW, int KG = 1>
-__global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs a) {
+__device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by, int bz, int grid_y) {
   using C = Bf16Cfg<D, NW, KG>;
   static_assert(KG == 1 || KG == 2, "one or two key groups");
   constexpr int ND = D / 16;   // k-steps of the S^T product
@@ -154,9 +157,9 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
   // and (2) map_batch puts the query heads that share a K/V stream on the same XCD, next to each other,
   // where they find its tiles in that XCD's L2.
   int kvh, batch, qt;
-  map_block(a, CAUSAL, &kvh, &batch, &qt);
+  map_block(a, CAUSAL, bx, by, grid_y, &kvh, &batch, &qt);
   const int q0 = qt * C::BQ;
-  const int split = blockIdx.z;
+  const int split = bz;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + C::BQ) : min(a.m, kv_begin + a.chunk);
   const int n_tiles = (kv_end - kv_begin + C::BKT - 1) / C::BKT;
@@ -392,6 +395,31 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
   if (r < a.rows && h == 0) lp0[rw] = (m_run + __log2f(l_tot)) * kLn2;
 }
 
+template <int D, bool CAUSAL, int NW, int KG = 1>
+__global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs a) {
+  attn_bf16_body<D, CAUSAL, NW, KG>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y);
+}
+
+// Both attentions of the path in ONE launch (same head dimension, same workgroup shape).  The query attention's
+// workgroups come first in the linear order and each walks ALL keys for its rows (no key chunks, no partial results,
+// no merge): such a workgroup lasts as long as the causal problem's longest row tile, which is handed out right
+// behind it, so the query attention hides inside the causal one instead of waiting for it.  n_q_pad, the query
+// workgroups rounded up to a multiple of 8, keeps the causal workgroups on the XCD slots map_block assumes.
+struct PairGrid {
+  int n_q, n_q_pad, q_gx, q_gy, c_gx, c_gy;
+};
+template <int D, int NW, int KG>
+__global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16_pair(AttnArgs ac, AttnArgs aq, PairGrid g) {
+  const int bid = blockIdx.x;
+  if (bid < g.n_q_pad) {
+    if (bid >= g.n_q) return;
+    attn_bf16_body<D, false, NW, KG>(aq, bid % g.q_gx, bid / g.q_gx, 0, g.q_gy);
+  } else {
+    const int l = bid - g.n_q_pad;
+    attn_bf16_body<D, true, NW, KG>(ac, l % g.c_gx, l / g.c_gx, 0, g.c_gy);
+  }
+}
+
 // ------------------------------------------------------ bf16, d = 128, asynchronous tile loads (LDS DMA)
 // Eight waves x 32 rows, one workgroup per compute unit; same arithmetic and operand layouts as
 // k_attn_bf16, with two changes to how a step is organised.
@@ -420,7 +448,7 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs
 // is free, so the swizzle costs nothing on the load side; on the read side it is folded into per-lane address
 // registers.
 template <bool CAUSAL>
-__global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
+__device__ __forceinline__ void attn_bf16_dma_body(const AttnArgs a, int bx, int by, int bz, int grid_y) {
   constexpr int D = 128, NW = 8, BQ = 32 * NW, BK = 64;
   constexpr int ND = D / 16, NV = D / 32;
   constexpr int TILE = BK * D * 2;  // 16 KB, unpadded
@@ -432,9 +460,9 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int rw = lane & 31, h = lane >> 5;
   int kvh, batch, qt;
-  map_block(a, CAUSAL, &kvh, &batch, &qt);
+  map_block(a, CAUSAL, bx, by, grid_y, &kvh, &batch, &qt);
   const int q0 = qt * BQ;
-  const int split = blockIdx.z;
+  const int split = bz;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
   const int kv_end = CAUSAL ? min(a.m, q0 + BQ) : min(a.m, kv_begin + a.chunk);
   const int span = kv_end - kv_begin;
@@ -694,6 +722,23 @@ __global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
   if (r < a.rows && h == 0) lp0[rw] = (m_ref + __log2f(l_tot)) * kLn2;
 }
 
+template <bool CAUSAL>
+__global__ __launch_bounds__(512, 2) void k_attn_bf16_dma(AttnArgs a) {
+  attn_bf16_dma_body<CAUSAL>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y);
+}
+
+// the pair launch (see k_attn_bf16_pair) of the asynchronous kernel
+__global__ __launch_bounds__(512, 2) void k_attn_bf16_dma_pair(AttnArgs ac, AttnArgs aq, PairGrid g) {
+  const int bid = blockIdx.x;
+  if (bid < g.n_q_pad) {
+    if (bid >= g.n_q) return;
+    attn_bf16_dma_body<false>(aq, bid % g.q_gx, bid / g.q_gx, 0, g.q_gy);
+  } else {
+    const int l = bid - g.n_q_pad;
+    attn_bf16_dma_body<true>(ac, l % g.c_gx, l / g.c_gx, 0, g.c_gy);
+  }
+}
+
 // ------------------------------------------------------------------------------------------- f32
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
@@ -705,7 +750,7 @@ __global__ __launch_bounds__(256) void k_attn_f32(AttnArgs a) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int kx = lane & 31, ch = lane >> 5;
   int kvh, batch, qt;
-  map_block(a, CAUSAL, &kvh, &batch, &qt);
+  map_block(a, CAUSAL, blockIdx.x, blockIdx.y, gridDim.y, &kvh, &batch, &qt);
   const int q0 = qt * RB;
   const int split = blockIdx.z;
   const int kv_begin = CAUSAL ? 0 : split * a.chunk;
@@ -857,6 +902,11 @@ hipError_t raise_lds_limit() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, Bf16Cfg<D, NW, KG>::LDS_BYTES);
 }
+template <int D, int NW, int KG>
+hipError_t raise_lds_limit_pair() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_pair<D, NW, KG>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, Bf16Cfg<D, NW, KG>::LDS_BYTES);
+}
 
 template <int D, bool CAUSAL, int NW, int KG = 1>
 hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
@@ -875,19 +925,73 @@ hipError_t run_bf16_dma(const AttnLaunch& l, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int D, bool CAUSAL>
-hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
-  // the asynchronous kernel serves the long causal problems (d = 128, enough row tiles for 8 waves)
-  if constexpr (D == 128) {
-    if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16_dma<CAUSAL>(l, s);
-  }
-  if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return run_bf16<D, CAUSAL, 8>(l, s);
+// Which bf16 kernel serves a problem.
+enum class Shape { kDma, kWaves8, kWaves8Keys2, kWaves4 };
+Shape bf16_shape(const AttnLaunch& l) {
+  // the asynchronous kernel serves the long problems (d = 128, enough row tiles for 8 waves)
+  if (attn_bf16_waves(l.causal, l.n_batch, l.rows) == 8) return l.d == 128 ? Shape::kDma : Shape::kWaves8;
   // short causal problems (at most two workgroups per compute unit): 128 rows per workgroup as with four waves, but
   // two key groups halve the chain of steps of the longest row tile, which is what such a launch waits for
-  if constexpr (CAUSAL) {
-    if (l.rows > 256 && (long long)l.n_batch * ((l.rows + 127) / 128) <= 512) return run_bf16<D, CAUSAL, 8, 2>(l, s);
+  if (l.causal && l.rows > 256 && (long long)l.n_batch * ((l.rows + 127) / 128) <= 512) return Shape::kWaves8Keys2;
+  return Shape::kWaves4;
+}
+
+template <int D, bool CAUSAL>
+hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
+  switch (bf16_shape(l)) {
+    case Shape::kDma:
+      if constexpr (D == 128) return run_bf16_dma<CAUSAL>(l, s);
+      return hipErrorInvalidValue;
+    case Shape::kWaves8: return run_bf16<D, CAUSAL, 8>(l, s);
+    case Shape::kWaves8Keys2:
+      if constexpr (CAUSAL) return run_bf16<D, CAUSAL, 8, 2>(l, s);
+      return hipErrorInvalidValue;
+    default: return run_bf16<D, CAUSAL, 4>(l, s);
   }
-  return run_bf16<D, CAUSAL, 4>(l, s);
+}
+
+// Pair launch: the query problem takes the causal problem's kernel shape and walks all keys in one chunk.
+bool pair_grid(AttnArgs* ac, AttnArgs* aq, int bq, PairGrid* g, unsigned* total) {
+  const dim3 gc = attn_grid(ac, (ac->rows + bq - 1) / bq), gq = attn_grid(aq, (aq->rows + bq - 1) / bq);
+  g->c_gx = (int)gc.x; g->c_gy = (int)gc.y; g->q_gx = (int)gq.x; g->q_gy = (int)gq.y;
+  const long long n_q = (long long)gq.x * gq.y, n_c = (long long)gc.x * gc.y;
+  const long long n_q_pad = (n_q + 7) / 8 * 8;
+  if (n_q_pad + n_c > 0x7FFFFFFFll) return false;
+  g->n_q = (int)n_q; g->n_q_pad = (int)n_q_pad;
+  *total = (unsigned)(n_q_pad + n_c);
+  return true;
+}
+
+template <int D, int NW, int KG>
+hipError_t run_pair(const AttnLaunch& c, const AttnLaunch& q, hipStream_t s) {
+  using C = Bf16Cfg<D, NW, KG>;
+  AttnArgs ac = make_args(c), aq = make_args(q);
+  PairGrid g;
+  unsigned total;
+  if (!pair_grid(&ac, &aq, C::BQ, &g, &total)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_attn_bf16_pair<D, NW, KG>), dim3(total), dim3(C::NT), C::LDS_BYTES, s, ac, aq, g);
+  return hipGetLastError();
+}
+
+hipError_t run_pair_dma(const AttnLaunch& c, const AttnLaunch& q, hipStream_t s) {
+  AttnArgs ac = make_args(c), aq = make_args(q);
+  PairGrid g;
+  unsigned total;
+  if (!pair_grid(&ac, &aq, 256, &g, &total)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_attn_bf16_dma_pair, dim3(total), dim3(512), kDmaLdsBytes, s, ac, aq, g);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t run_pair_d(const AttnLaunch& c, const AttnLaunch& q, hipStream_t s) {
+  switch (bf16_shape(c)) {
+    case Shape::kDma:
+      if constexpr (D == 128) return run_pair_dma(c, q, s);
+      return hipErrorInvalidValue;
+    case Shape::kWaves8: return run_pair<D, 8, 1>(c, q, s);
+    case Shape::kWaves8Keys2: return run_pair<D, 8, 2>(c, q, s);
+    default: return run_pair<D, 4, 1>(c, q, s);
+  }
 }
 
 template <int D, bool CAUSAL>
@@ -921,6 +1025,10 @@ hipError_t attn_prepare_device() {
       hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<true>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes),
       hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<false>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes),
+      raise_lds_limit_pair<128, 8, 1>(),   raise_lds_limit_pair<128, 8, 2>(), raise_lds_limit_pair<128, 4, 1>(),
+      raise_lds_limit_pair<64, 8, 1>(),    raise_lds_limit_pair<64, 8, 2>(),  raise_lds_limit_pair<64, 4, 1>(),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma_pair),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes)};
   for (hipError_t x : all)
     if (x != hipSuccess) return x;
@@ -933,6 +1041,17 @@ hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
   if (e != hipSuccess) return e;
   if (l.d == 128) return l.causal ? run_bf16_nw<128, true>(l, s) : run_bf16_nw<128, false>(l, s);
   return l.causal ? run_bf16_nw<64, true>(l, s) : run_bf16_nw<64, false>(l, s);
+}
+
+hipError_t launch_attn_bf16_pair(const AttnLaunch& causal, const AttnLaunch& query, hipStream_t s) {
+  const hipError_t e = attn_prepare_device();
+  if (e != hipSuccess) return e;
+  AttnLaunch q = query;
+  q.n_split = 1;
+  q.chunk = q.m;
+  q.part_o = nullptr;
+  q.part_lse = nullptr;
+  return causal.d == 128 ? run_pair_d<128>(causal, q, s) : run_pair_d<64>(causal, q, s);
 }
 
 hipError_t launch_attn_f32(const AttnLaunch& l, hipStream_t s) {

@@ -125,6 +125,9 @@ struct AttnLaunch {
   float* part_lse;     // [n_split][n_batch][rows]
 };
 hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
+// Both bf16 attentions of the path in one launch: `causal` and `query` share d, K and the prepared V; the query
+// attention runs without key chunks whatever `query` says (its n_split, chunk and partial buffers are ignored).
+hipError_t launch_attn_bf16_pair(const AttnLaunch& causal, const AttnLaunch& query, hipStream_t s);
 hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attn_merge(const AttnLaunch& a, hipStream_t s);
 

@@ -808,8 +808,12 @@ int samkv_recompute_query_attn(const void* q_rec, const void* q_tok, int32_t n_q
   hipError_t e = prepare_v(&rec, w.vp, static_cast<char*>(ws) + w.vp_at, n_kv_heads, s);
   qry.v = rec.v;
   qry.v_unscale = rec.v_unscale;
-  if (e == hipSuccess) e = run_attn(rec, s);
-  if (e == hipSuccess) e = run_attn(qry, s);
+  if (dtype == SAMKV_BF16) {
+    if (e == hipSuccess) e = launch_attn_bf16_pair(rec, qry, s);
+  } else {
+    if (e == hipSuccess) e = run_attn(rec, s);
+    if (e == hipSuccess) e = run_attn(qry, s);
+  }
   return dev(e);
 }
 

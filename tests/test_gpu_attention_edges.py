@@ -117,6 +117,49 @@ def test_query_attention_with_self_tail(dtype, d, hq, hkv, lq, m):
     assert torch.isfinite(out).all()
 
 
+@pytest.mark.parametrize("dtype,d,hq,hkv,lq,m", [
+    # one launch for both attentions, in every workgroup shape the causal problem can select (the query attention
+    # takes the same shape and walks all keys in one chunk): 128 rows x two key groups, four waves, the asynchronous
+    # kernel with KV heads in groups of 8 / in three such groups / not a multiple of 8, eight waves at d = 64
+    ("bf16", 128, 32, 8, 32, 1540), ("bf16", 128, 8, 2, 5, 200), ("bf16", 128, 4, 4, 1, 1),
+    ("bf16", 128, 64, 8, 256, 4200), ("bf16", 128, 48, 24, 7, 2300), ("bf16", 128, 40, 10, 33, 2600),
+    ("bf16", 64, 64, 8, 130, 4200), ("bf16", 64, 16, 4, 64, 449), ("bf16", 64, 8, 2, 3, 100),
+    ("bf16", 128, 32, 8, 300, 700),      # more query rows than one workgroup holds, short cache
+    ("f32", 64, 8, 2, 16, 156),          # float32: the call runs the two kernels one after the other
+])
+def test_both_attentions_in_one_call(dtype, d, hq, hkv, lq, m):
+    """samkv_recompute_query_attn against the two separate calls and the oracle: the recompute attention runs the same
+    arithmetic in the same order (same bits); the query attention walks the keys in one chunk instead of several
+    (same definition, different rounding), so it is held against the oracle and must stay within the bar of the
+    separate call's result as well."""
+    import torch
+    from paper_2508_11661_amd import samkv as S
+    q, k, v = _data(3 * m + hq, dtype, hq, hkv, m, m, d)
+    qt = synth.round_to_dtype(np.random.default_rng(5 * m + lq).standard_normal((hq, lq, d), dtype=np.float32) * 1.5, dtype)
+    scale = 1.0 / math.sqrt(d)
+    dev = [H.to_dev(x, dtype) for x in (q, qt, k, v)]
+    nan = lambda *shape: torch.full(shape, float("nan"), device="cuda")
+    ro, rl, qo, ql = nan(hq, m, d), nan(hq, m), nan(hq, lq, d), nan(hq, lq)
+    ro2, rl2, qo2, ql2 = nan(hq, m, d), nan(hq, m), nan(hq, lq, d), nan(hq, lq)
+    ws = torch.empty((S.samkv_workspace_bytes(1, hq, hkv, d, lq, m),), dtype=torch.uint8, device="cuda")
+    S.samkv_recompute_query_attn(dev[0], dev[1], dev[2], dev[3], scale, ro, rl, qo, ql, ws)
+    S.samkv_recompute_attn(dev[0], dev[2], dev[3], scale, ro2, rl2, ws)
+    S.samkv_query_attn(dev[1], dev[2], dev[3], scale, qo2, ql2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ro, ro2) and torch.equal(rl, rl2), "recompute attention: pair call and separate call differ"
+    if dtype == "f32":
+        assert torch.equal(qo, qo2) and torch.equal(ql, ql2)
+    else:
+        assert (qo - qo2).abs().max().item() <= H.BF16_ABS and (ql - ql2).abs().max().item() <= H.BF16_ABS
+    rows = _rows(lq, 24 if hq * lq * m > 3e7 else lq, seed=m)
+    rows = None if rows is None else rows[rows < lq]
+    o_ref, l_ref = O.attention(qt, k, v, scale, False, rows=rows)
+    sel = slice(None) if rows is None else torch.from_numpy(rows).cuda()
+    H.check_attention(qo[:, sel].cpu().numpy(), ql[:, sel].cpu().numpy(), o_ref, l_ref, dtype,
+                      f"query in the pair call {dtype} d={d} hq={hq} lq={lq} m={m}")
+    assert torch.isfinite(qo).all() and torch.isfinite(ql).all() and torch.isfinite(ro).all()
+
+
 @pytest.mark.parametrize("log2_scale", [-40, -20, 0, 7, 30, 100])
 @pytest.mark.parametrize("causal", [True, False])
 def test_bf16_attention_value_magnitudes(log2_scale, causal):

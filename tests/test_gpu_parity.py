@@ -101,12 +101,21 @@ def _stages(S, x, ratio, n_sink=0, n_local=0, use_bias=True, q_rec_seed_rows=Non
     H.check_chained(x, ref, idx_chain, buf.k_c.float().cpu().numpy(), buf.v_c.float().cpu().numpy(),
                     buf.rec_out.cpu().numpy(), buf.rec_lse.cpu().numpy(), buf.q_out.cpu().numpy(), buf.q_lse.cpu().numpy(),
                     q_rec_np, scale)
-    # ---- the fused calls (score+select+gather, both attentions) and the five separate calls: the same bits
+    # ---- the fused calls (score+select+gather, both attentions) and the five separate calls: the same bits, except
+    #      for the bf16 query attention, which the pair call computes over all keys in one chunk and the separate call
+    #      in several that it merges (both were just held against the oracle; here: within the bar of each other)
     buf2 = S.alloc_layer_buffers(caches, w.n_q_tok, ratio)
     S.hot_path(caches, q_tok, q_loc, q_rec, ratio, scale, buf2, n_sink, n_local, fused=False)
     torch.cuda.synchronize()
     for name in ("idx", "k_c", "v_c", "rec_out", "rec_lse", "q_out", "q_lse"):
-        assert torch.equal(getattr(buf, name), getattr(buf2, name)), f"fused and separate calls differ in {name}"
+        a, b = getattr(buf, name), getattr(buf2, name)
+        if dt == "bf16" and name in ("q_out", "q_lse"):
+            assert (a - b).abs().max().item() <= H.BF16_ABS, f"fused and separate calls differ in {name}"
+        else:
+            assert torch.equal(a, b), f"fused and separate calls differ in {name}"
+    H.check_chained(x, ref, idx_chain, buf2.k_c.float().cpu().numpy(), buf2.v_c.float().cpu().numpy(),
+                    buf2.rec_out.cpu().numpy(), buf2.rec_lse.cpu().numpy(), buf2.q_out.cpu().numpy(),
+                    buf2.q_lse.cpu().numpy(), q_rec_np, scale, what="separate calls")
     return dict(in_margin=in_margin, clean=len(clean_heads), e_rec=e_rec, e_q=e_q, m=m)
 
 
