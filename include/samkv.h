@@ -282,10 +282,13 @@ int samkv_recompute_attn(const void* q_rec, const void* k_c, const void* v_c, in
  * cached token precedes the query, so there is no mask):
  *   out[h][t][:] = sum_{j < M} softmax_j(scale * <q_tok[h][t], k_c[g][j]>) * v_c[g][j],  lse likewise.
  *   q_tok [Hq][n_q_tok][d]; out [Hq][n_q_tok][d], lse [Hq][n_q_tok] float32.
- * Arithmetic as in samkv_recompute_attn.  Long caches are cut into key chunks whose partial results are merged by
- * their log-sum-exp, in chunk order (deterministic).
- * ws: samkv_workspace_bytes(...) bytes, 256-byte aligned: the half-precision copy of V (bf16) and the chunk
- * partials; f32 with a single chunk needs none.  Too small or missing: SAMKV_EWORKSPACE. */
+ * Arithmetic as in samkv_recompute_attn, with one difference for bf16 with fewer than 512 query rows per KV head
+ * (G * n_q_tok < 512: the call is bound by latency or by HBM, and rewriting V would cost more than the products):
+ * V is read as stored and every softmax weight enters the second product as the sum of two bf16 terms
+ * (16 significant bits), on the bf16 matrix cores; no copy of V is made.  Long caches are cut into key chunks whose
+ * partial results are merged by their log-sum-exp, in chunk order (deterministic).
+ * ws: samkv_workspace_bytes(...) bytes, 256-byte aligned: the half-precision copy of V (bf16, when made) and the
+ * chunk partials; f32 with a single chunk needs none.  Too small or missing: SAMKV_EWORKSPACE. */
 int samkv_query_attn(const void* q_tok, int32_t n_q_tok, const void* k_c, const void* v_c,
                      int32_t m_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                      int32_t dtype, float scale, float* out, float* lse, void* ws, size_t ws_bytes,

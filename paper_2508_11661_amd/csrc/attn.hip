@@ -137,12 +137,20 @@ struct Bf16Cfg {
   static constexpr int LDS_BYTES = 2 * TILE_BYTES;
   static constexpr int CHUNKS = (BKT * D * 2 / 16) / NT;  // 16-byte chunks per thread per tile and tensor
   static constexpr int MERGE_BYTES = RG * 64 * (D / 32 * 16 + 2) * 4;  // one key group's state per row group
+
   static_assert(KG == 1 || MERGE_BYTES <= LDS_BYTES, "the merge reuses the tile buffers");
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int D, bool CAUSAL, int NW, int KG = 1>
+// SPLIT: how the second product gets 16-bit operands without losing the weights' precision.  false: the weights are
+// rounded to half precision and V is the scaled half-precision copy that vprep.hip makes.  true: V is read as stored
+// (bf16) and every weight travels as the sum of TWO bf16 terms (p = hi + lo, 16 significant bits), which doubles the
+// second product's instructions and needs no copy.  That pays where the products are not what the kernel waits for
+// and the launches that prepare V would cost more: the query attention of short and mid-size caches (bound by
+// latency or by HBM; 34 -> 26 us at M = 1540, 54 -> 45 us at M = 6160 as calls).  Causal problems of the same shapes
+// lose more in the products than the preparation costs (+10 to +18 % at M = 2304 .. 2816) and keep the copy.
+template <int D, bool CAUSAL, int NW, int KG = 1, bool SPLIT = false>
 __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by, int bz, int grid_y) {
   using C = Bf16Cfg<D, NW, KG>;
   static_assert(KG == 1 || KG == 2, "one or two key groups");
@@ -288,9 +296,11 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by,
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) s[kb][j] = __builtin_amdgcn_exp2f(fmaf(s[kb][j], c2, -m_use));
-      // weights go to half precision for the second product; their row sum is taken over the ROUNDED weights
-      // (pair . (1,1) accumulated in float32), so numerator and denominator see the same weights
+      // Half-precision weights: their row sum is taken over the ROUNDED weights (pair . (1,1) accumulated in
+      // float32), so numerator and denominator see the same weights.  Two-term bf16 weights: hi = bf16(p),
+      // lo = bf16(p - hi); hi + lo is p to 2^-17, and the row sum is the plain float32 sum of p.
       f16x8 bp[2][2];
+      bf16x8 bhi[2][2], blo[2][2];
       float psum = 0.f;
       const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
@@ -299,10 +309,21 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by,
         for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
           for (int e = 0; e < 8; e += 2) {
-            f16x2 pr = {(_Float16)s[kb][8 * s2 + e], (_Float16)s[kb][8 * s2 + e + 1]};
-            bp[kb][s2][e] = pr[0];
-            bp[kb][s2][e + 1] = pr[1];
-            psum = __builtin_amdgcn_fdot2(pr, ones, psum, false);
+            const float p0 = s[kb][8 * s2 + e], p1 = s[kb][8 * s2 + e + 1];
+            if constexpr (SPLIT) {
+              const bf16x2 hi = {(__bf16)p0, (__bf16)p1};
+              const bf16x2 lo = {(__bf16)(p0 - (float)hi[0]), (__bf16)(p1 - (float)hi[1])};
+              bhi[kb][s2][e] = hi[0];
+              bhi[kb][s2][e + 1] = hi[1];
+              blo[kb][s2][e] = lo[0];
+              blo[kb][s2][e + 1] = lo[1];
+              psum += p0 + p1;
+            } else {
+              f16x2 pr = {(_Float16)p0, (_Float16)p1};
+              bp[kb][s2][e] = pr[0];
+              bp[kb][s2][e + 1] = pr[1];
+              psum = __builtin_amdgcn_fdot2(pr, ones, psum, false);
+            }
           }
       l_run = fmaf(l_run, alpha, psum);
       if (__any(alpha != 1.f)) {
@@ -322,10 +343,15 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by,
             const char* vp = sv + key1 * C::VSTR + (dvb * 32 + q2 * 16 + 4 * (i16 & 3)) * 2;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * C::VSTR));
-            union { struct { s16x4 lo, hi; } s; f16x8 v; } av;
+            union { struct { s16x4 lo, hi; } s; f16x8 v; bf16x8 b; } av;
             av.s.lo = lo;
             av.s.hi = hi;
-            o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
+            if constexpr (SPLIT) {
+              o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.b, bhi[kb][s2], o[dvb], 0, 0, 0);
+              o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av.b, blo[kb][s2], o[dvb], 0, 0, 0);
+            } else {
+              o[dvb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av.v, bp[kb][s2], o[dvb], 0, 0, 0);
+            }
           }
         }
     }
@@ -360,7 +386,9 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by,
   }
 
   const float l_tot = sum_across_halves(l_run);
-  const float inv = a.v_unscale[kvh] / l_tot;
+  float v_unscale = 1.f;
+  if constexpr (!SPLIT) v_unscale = a.v_unscale[kvh];
+  const float inv = v_unscale / l_tot;
   const size_t row0 = (size_t)batch * a.rows + wave_first;
   float* op0;
   float* lp0;
@@ -395,9 +423,9 @@ __device__ __forceinline__ void attn_bf16_body(const AttnArgs a, int bx, int by,
   if (r < a.rows && h == 0) lp0[rw] = (m_run + __log2f(l_tot)) * kLn2;
 }
 
-template <int D, bool CAUSAL, int NW, int KG = 1>
+template <int D, bool CAUSAL, int NW, int KG = 1, bool SPLIT = false>
 __global__ __launch_bounds__(64 * NW, KG == 1 ? 2 : 1) void k_attn_bf16(AttnArgs a) {
-  attn_bf16_body<D, CAUSAL, NW, KG>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y);
+  attn_bf16_body<D, CAUSAL, NW, KG, SPLIT>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y);
 }
 
 // Both attentions of the path in ONE launch (same head dimension, same workgroup shape).  The query attention's
@@ -897,9 +925,9 @@ dim3 attn_grid(AttnArgs* a, int tiles) {
 
 constexpr int kDmaLdsBytes = 6 * 64 * 256;
 
-template <int D, bool CAUSAL, int NW, int KG = 1>
+template <int D, bool CAUSAL, int NW, int KG = 1, bool SPLIT = false>
 hipError_t raise_lds_limit() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16<D, CAUSAL, NW, KG, SPLIT>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, Bf16Cfg<D, NW, KG>::LDS_BYTES);
 }
 template <int D, int NW, int KG>
@@ -908,12 +936,12 @@ hipError_t raise_lds_limit_pair() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, Bf16Cfg<D, NW, KG>::LDS_BYTES);
 }
 
-template <int D, bool CAUSAL, int NW, int KG = 1>
+template <int D, bool CAUSAL, int NW, int KG = 1, bool SPLIT = false>
 hipError_t run_bf16(const AttnLaunch& l, hipStream_t s) {
   using C = Bf16Cfg<D, NW, KG>;
   AttnArgs a = make_args(l);
   dim3 grid = attn_grid(&a, (l.rows + C::BQ - 1) / C::BQ);
-  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW, KG>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((k_attn_bf16<D, CAUSAL, NW, KG, SPLIT>), grid, dim3(C::NT), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -938,6 +966,7 @@ Shape bf16_shape(const AttnLaunch& l) {
 
 template <int D, bool CAUSAL>
 hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
+  if (attn_bf16_reads_v16(l) != (l.v_unscale != nullptr)) return hipErrorInvalidValue;  // V prepared iff the shape reads the copy
   switch (bf16_shape(l)) {
     case Shape::kDma:
       if constexpr (D == 128) return run_bf16_dma<CAUSAL>(l, s);
@@ -946,7 +975,9 @@ hipError_t run_bf16_nw(const AttnLaunch& l, hipStream_t s) {
     case Shape::kWaves8Keys2:
       if constexpr (CAUSAL) return run_bf16<D, CAUSAL, 8, 2>(l, s);
       return hipErrorInvalidValue;
-    default: return run_bf16<D, CAUSAL, 4>(l, s);
+    default:
+      if constexpr (CAUSAL) return run_bf16<D, true, 4>(l, s);
+      return run_bf16<D, false, 4, 1, true>(l, s);  // two-term weights, V as stored
   }
 }
 
@@ -1019,8 +1050,8 @@ hipError_t attn_prepare_device() {
   if (done[dev]) return hipSuccess;
   const hipError_t all[] = {
       raise_lds_limit<128, true, 8>(),     raise_lds_limit<128, false, 8>(), raise_lds_limit<128, true, 4>(),
-      raise_lds_limit<128, false, 4>(),    raise_lds_limit<128, true, 8, 2>(), raise_lds_limit<64, true, 8>(),
-      raise_lds_limit<64, false, 8>(),     raise_lds_limit<64, true, 4>(),   raise_lds_limit<64, false, 4>(),
+      raise_lds_limit<128, false, 4, 1, true>(), raise_lds_limit<128, true, 8, 2>(), raise_lds_limit<64, true, 8>(),
+      raise_lds_limit<64, false, 8>(),     raise_lds_limit<64, true, 4>(),   raise_lds_limit<64, false, 4, 1, true>(),
       raise_lds_limit<64, true, 8, 2>(),
       hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_bf16_dma<true>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes),
@@ -1036,6 +1067,8 @@ hipError_t attn_prepare_device() {
   return hipSuccess;
 }
 
+bool attn_bf16_reads_v16(const AttnLaunch& l) { return l.causal || bf16_shape(l) != Shape::kWaves4; }
+
 hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
   const hipError_t e = attn_prepare_device();
   if (e != hipSuccess) return e;
@@ -1046,6 +1079,7 @@ hipError_t launch_attn_bf16(const AttnLaunch& l, hipStream_t s) {
 hipError_t launch_attn_bf16_pair(const AttnLaunch& causal, const AttnLaunch& query, hipStream_t s) {
   const hipError_t e = attn_prepare_device();
   if (e != hipSuccess) return e;
+  if (causal.v_unscale == nullptr || query.v != causal.v) return hipErrorInvalidValue;  // both read the prepared copy
   AttnLaunch q = query;
   q.n_split = 1;
   q.chunk = q.m;

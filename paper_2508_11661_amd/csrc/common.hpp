@@ -115,8 +115,8 @@ struct AttnLaunch {
   int n_batch, batch_per_kv, rows, m;
   const void* q;   // [n_batch][rows][d]
   const void* k;   // [n_batch / batch_per_kv][m][d]
-  const void* v;   // bf16 kernels: the half-precision copy that launch_v_prep wrote; f32 kernel: V itself
-  const float* v_unscale;  // bf16 kernels: [n_batch / batch_per_kv] factor that undoes the copy's power-of-two scale
+  const void* v;   // bf16 kernels that read the copy (attn_bf16_reads_v16): what launch_v_prep wrote; otherwise V itself
+  const float* v_unscale;  // with the copy: [n_batch / batch_per_kv] factors that undo its power-of-two scale; else null
   float* out;      // [n_batch][rows][d]
   float* lse;      // [n_batch][rows]
   float scale;
@@ -125,6 +125,10 @@ struct AttnLaunch {
   float* part_lse;     // [n_split][n_batch][rows]
 };
 hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
+// Whether the bf16 kernel that serves this problem reads the scaled half-precision copy of V (every causal problem,
+// long problems that are not causal) or V as stored (the four-wave kernel of a problem that is not causal).  A pair
+// launch always reads the copy.
+bool attn_bf16_reads_v16(const AttnLaunch& a);
 // Both bf16 attentions of the path in one launch: `causal` and `query` share d, K and the prepared V; the query
 // attention runs without key chunks whatever `query` says (its n_split, chunk and partial buffers are ignored).
 hipError_t launch_attn_bf16_pair(const AttnLaunch& causal, const AttnLaunch& query, hipStream_t s);

@@ -169,7 +169,7 @@ AttnWs attn_ws(int dtype, bool causal, int hkv, int rows_per_kv, int m, int d) {
 
 // Runs the V preparation of a bf16 attention call into its workspace slice and points the launch at the copy.
 hipError_t prepare_v(AttnLaunch* a, const VPrepWs& vp, char* at, int hkv, hipStream_t s) {
-  if (a->dtype != SAMKV_BF16) return hipSuccess;
+  if (a->dtype != SAMKV_BF16 || !attn_bf16_reads_v16(*a)) return hipSuccess;
   float* unscale = reinterpret_cast<float*>(at + vp.unscale);
   const hipError_t e = launch_v_prep(a->v, hkv, a->m, a->d, at + vp.v16, reinterpret_cast<uint32_t*>(at + vp.part), unscale, s);
   a->v = at + vp.v16;
