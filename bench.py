@@ -419,6 +419,102 @@ class Workbench:
         return ms
 
 
+def next_rows(samkv, wb, iters=20, warmup=3):
+    """The entry points beyond the five of the step (cache update, block-level retrieval with the cross-document
+    filter, gathers by explicit counts / global positions / of the Q caches, query attention with its own tail), each
+    timed alone on the workload's shapes: median of `iters` event-bracketed calls after `warmup`.  HBM-bound rows
+    report their algorithmic bytes against the HBM peak; the small selection kernels are latency-bound."""
+    import numpy as np
+    import torch
+    w, S = wb.w, samkv
+    if wb.stacked or w.dtype != "bf16":
+        return None
+    s, b = wb.sets[0], wb.bufs[0]
+    caches = s["caches"]
+    n, hq, hkv, d, e = w.n_ctx, w.n_q_heads, w.n_kv_heads, w.head_dim, 2
+    total, m, block = sum(w.lens), wb.m, 64
+    gen = torch.Generator(device="cuda").manual_seed(0x5A4D)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda", generator=gen).to(torch.bfloat16)
+
+    # the calls repeat on the same buffers: a 512 MB copy ahead of every timed call pushes them out of the 256 MB
+    # Infinity Cache, so that every call finds its inputs in HBM as it would inside a step
+    flush_src = torch.empty((512 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+    flush_dst = torch.empty_like(flush_src)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        ev = []
+        for _ in range(iters):
+            flush_dst.copy_(flush_src)
+            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            z.record()
+            ev.append((a, z))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(z) for a, z in ev]))
+
+    def row(ms, nbytes=None, flops=None):
+        r = {"us": round(ms * 1e3, 1)}
+        if nbytes is not None:
+            r["GB/s"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+            r["frac_hbm"] = round(r["GB/s"] / HBM_PEAK_GBS, 4)
+        if flops is not None:
+            r["TFLOP/s"] = round(flops / (ms * 1e-3) / 1e12, 1)
+            r["frac_mfma"] = round(r["TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS, 4)
+        return r
+
+    out = {"workload": w.name, "block": block, "note": "each call alone, inputs resident in HBM; a 512 MB device copy "
+           "ahead of every timed call empties the 256 MB Infinity Cache"}
+    wb.step(0)                                   # the compacted cache and the buffers hold a step's results
+    S.samkv_score(caches, s["q_tok"], s["q_loc"], b.scores, b.ws)
+    torch.cuda.synchronize()
+    # ---- cache update after recomputation (Eq. 4): rows of the compacted cache against new rows
+    k_new, v_new = rnd(hkv, m, d), rnd(hkv, m, d)
+    rows_bytes = 2 * hkv * m * d * e             # K and V
+    out["kv_update_overwrite"] = row(timed(lambda: S.samkv_kv_update(b.k_c, b.v_c, k_new, v_new, 0)), 2 * rows_bytes)
+    out["kv_update_fusion"] = row(timed(lambda: S.samkv_kv_update(b.k_c, b.v_c, k_new, v_new, 1)), 3 * rows_bytes)
+    # ---- block-level retrieval (64-token blocks, one initial and two local blocks forced, share 0.15 of the rest)
+    n_blk = sum(-(-x // block) for x in w.lens)
+    bscores = torch.empty((hkv, n_blk), dtype=torch.float32, device="cuda")
+    out["block_scores"] = row(timed(lambda: S.samkv_block_scores(b.scores, caches, block, bscores)),
+                              hkv * (total + n_blk) * 4)
+    p = [0.15] * n
+    ws_b = torch.empty((max(S.samkv_block_workspace_bytes(caches, block), 256),), dtype=torch.uint8, device="cuda")
+    m_b = S.samkv_block_select_count(caches, block, p, 1, 2)
+    idx_b = torch.empty((hkv, m_b), dtype=torch.int32, device="cuda")
+    cu = S.samkv_block_select(bscores, caches, block, p, 1, 2, idx_b, None, ws_b)
+    out["block_select"] = row(timed(lambda: S.samkv_block_select(bscores, caches, block, p, 1, 2, idx_b, None, ws_b)))
+    out["block_select"]["kept_tokens"] = m_b
+    k2 = torch.empty((hkv, m_b, d), dtype=torch.bfloat16, device="cuda")
+    v2 = torch.empty_like(k2)
+    gather_bytes = lambda mm: hkv * mm * (4 * d * e + 4)
+    out["gather_v"] = row(timed(lambda: S.samkv_gather_v(caches, idx_b, cu, k2, v2)), gather_bytes(m_b))
+    m_f = S.samkv_block_filter_count(caches, block, p, 1, 2)
+    gidx = torch.empty((hkv, m_f), dtype=torch.int32, device="cuda")
+    out["block_select_filter"] = row(timed(lambda: S.samkv_block_select_filter(bscores, caches, block, p, 1, 2, gidx, ws_b)))
+    out["block_select_filter"]["kept_tokens"] = m_f
+    k3 = torch.empty((hkv, m_f, d), dtype=torch.bfloat16, device="cuda")
+    v3 = torch.empty_like(k3)
+    out["gather_g"] = row(timed(lambda: S.samkv_gather_g(caches, gidx, k3, v3)), gather_bytes(m_f))
+    del k2, v2, k3, v3
+    # ---- the stored Q caches compacted at the kept positions of the step
+    q_cache = [rnd(hq, x, d) for x in w.lens]
+    q_rec = torch.empty((hq, m, d), dtype=torch.bfloat16, device="cuda")
+    out["gather_q"] = row(timed(lambda: S.samkv_gather_q(caches, q_cache, b.idx, wb.ratio, q_rec)),
+                          hq * m * 2 * d * e + hkv * m * 4)
+    del q_cache, q_rec
+    # ---- query attention with the query tokens' own K/V appended causally
+    lq = w.n_q_tok
+    k_self, v_self = rnd(hkv, lq, d), rnd(hkv, lq, d)
+    out["query_attn_self"] = row(timed(lambda: S.samkv_query_attn_self(s["q_tok"], b.k_c, b.v_c, k_self, v_self, wb.scale,
+                                                                       b.q_out, b.q_lse, b.ws)),
+                                 flops=4.0 * hq * d * lq * (m + (lq + 1) / 2))
+    return out
+
+
+
 def sweep(samkv, synth, iters=30, warmup=8):
     """The five separate calls of the path on `mistral_7b_sweep` at each of its budgets: score is flat in the budget,
     gather and the query attention grow with r, the recompute attention with r^2.  Per call: median of `iters`
@@ -468,6 +564,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     ap.add_argument("--no-secondary", action="store_true", help="skip the extra timing of the small llama3_8b_layer workload")
     ap.add_argument("--no-sweep", action="store_true", help="skip the budget sweep on mistral_7b_sweep")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the timing of the entry points beyond the step (cache update, block-level retrieval, ...)")
     ap.add_argument("--layout", choices=("stacked", "per-layer"), default="stacked",
                     help="multi-layer workloads: all layers in one tensor per document and one call per entry point, "
                          "or one set of calls per layer")
@@ -570,6 +668,10 @@ def main() -> int:
         out["hip_graph"] = {"ms_per_step": round(graph_ms, 4), "value": round(tokens / (graph_ms * 1e-3), 1),
                             "unit": "tokens/s", "note": "the same steps launched as replays of captured HIP graphs"}
     layer0 = wb.layers_np[0]
+    if not args.no_next_rows:
+        nr = next_rows(samkv, wb)
+        if nr is not None:
+            out["next_rows"] = nr
     del wb
     torch.cuda.empty_cache()
     if not args.no_secondary and w.name != "llama3_8b_layer":
