@@ -114,9 +114,12 @@ __device__ __forceinline__ void select_from_keys(uint32_t (&key)[E], int p0, int
   constexpr int NW = NT / 64;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   // ---- k-th largest key, bit by bit ------------------------------------------------------------
+  // `bucket` = positions < L whose keys agree with the bits decided so far; kk of them are still to be kept.  Once
+  // bucket == kk every one of them is kept whatever the remaining bits say, so the walk stops there (distinct keys:
+  // after about log2(L) bits below the ones all keys share; rows of equal keys walk all 32).
   uint32_t prefix = 0;
-  uint32_t kk = (uint32_t)k;
-  for (int b = 31; b >= 0; --b) {
+  uint32_t kk = (uint32_t)k, bucket = (uint32_t)L;
+  for (int b = 31; b >= 0 && bucket != kk; --b) {
     // candidate: agrees with the decided bits above b and has bit b set (padding keys are 0: never)
     const uint32_t want = (prefix >> b) | 1u;
     uint32_t c = 0;
@@ -127,10 +130,18 @@ __device__ __forceinline__ void select_from_keys(uint32_t (&key)[E], int p0, int
     uint32_t tot = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) tot += cnt[b & 1][w];
-    if (tot >= kk) prefix |= (1u << b); else kk -= tot;
+    if (tot >= kk) {
+      prefix |= (1u << b);
+      bucket = tot;
+    } else {
+      kk -= tot;
+      bucket -= tot;
+    }
   }
+  // T: the decided bits, zeros below.  Stopped early: every key >= T is kept; walked to the end: keys > T and the
+  // first kk positions with key == T
   const uint32_t T = prefix;
-  const uint32_t need = kk;  // how many positions with key == T are kept
+  const uint32_t need = bucket == kk ? 0xFFFFFFFFu : kk;  // how many positions with key == T are kept
 
   // ---- ordered compaction ------------------------------------------------------------------------
   uint32_t n_gt = 0, n_eq = 0;
